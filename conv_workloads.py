@@ -1,0 +1,141 @@
+"""Seeded synthetic convolution workloads.
+
+This module only *describes* layers and draws their tensors; it contains none of
+the convolution / Winograd arithmetic.  It is the one piece shared by the CPU
+oracle's tests and the HIP path's tests and benchmark, so that both sides see
+bit-identical inputs.
+
+The five workload families stand in for the networks the paper evaluates
+(MobileNet-v1, ResNet-18 and friends at one 224x224 image, Section 4.1): they
+take the *layer shapes* of those networks and fill them with seeded random
+tensors.  No dataset item, trained weight or model file is involved.
+
+Recipe (all workloads):
+  * generator   numpy ``Generator(PCG64(seed))``, seed = 200212418 + 1000*config + layer
+  * draw order  x, then w, then b  (float64 draws, rounded once to float32)
+  * x           uniform[lo, hi]   (``x_range`` of the workload)
+  * w           normal(0, sqrt(2 / (kh*kw*C_in)))      (He-normal)
+  * b           uniform[-0.1, 0.1]
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Tuple
+
+import numpy as np
+
+BASE_SEED = 200212418
+
+
+@dataclass(frozen=True)
+class ConvLayer:
+    """One 2-D convolution layer: NCHW input, KCRS weight, groups = 1."""
+    name: str
+    n: int
+    c_in: int
+    h: int
+    w: int
+    c_out: int
+    kh: int
+    kw: int
+    stride: int = 1
+    pad: int = 0
+    dil: int = 1
+    x_range: Tuple[float, float] = (-1.0, 1.0)
+    seed: int = BASE_SEED
+
+    @property
+    def h_out(self) -> int:
+        return (self.h + 2 * self.pad - self.dil * (self.kh - 1) - 1) // self.stride + 1
+
+    @property
+    def w_out(self) -> int:
+        return (self.w + 2 * self.pad - self.dil * (self.kw - 1) - 1) // self.stride + 1
+
+    @property
+    def direct_flops(self) -> int:
+        """2*N*K*C*H_o*W_o*kh*kw: the direct-convolution count every scheme is priced in."""
+        return 2 * self.n * self.c_out * self.c_in * self.h_out * self.w_out * self.kh * self.kw
+
+    def with_batch(self, n: int) -> "ConvLayer":
+        return ConvLayer(self.name, n, self.c_in, self.h, self.w, self.c_out, self.kh, self.kw,
+                         self.stride, self.pad, self.dil, self.x_range, self.seed)
+
+
+def draw(layer: ConvLayer, with_bias: bool = True):
+    """Return (x, w, b) as float32 numpy arrays for ``layer`` (b is None without bias)."""
+    rng = np.random.Generator(np.random.PCG64(layer.seed))
+    lo, hi = layer.x_range
+    x = rng.uniform(lo, hi, size=(layer.n, layer.c_in, layer.h, layer.w)).astype(np.float32)
+    sigma = float(np.sqrt(2.0 / (layer.kh * layer.kw * layer.c_in)))
+    w = rng.normal(0.0, sigma, size=(layer.c_out, layer.c_in, layer.kh, layer.kw)).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(layer.c_out,)).astype(np.float32)
+    return x, w, (b if with_bias else None)
+
+
+def _mk(cfg: int, idx: int, name: str, n, c, hw, k, ksz, stride, pad, x_range=(-1.0, 1.0)) -> ConvLayer:
+    return ConvLayer(name=name, n=n, c_in=c, h=hw, w=hw, c_out=k, kh=ksz, kw=ksz, stride=stride,
+                     pad=pad, dil=1, x_range=x_range, seed=BASE_SEED + 1000 * cfg + idx)
+
+
+def config_layers(cfg: int) -> List[ConvLayer]:
+    """The layers of workload family ``cfg`` (1..5)."""
+    if cfg == 1:
+        return [_mk(1, 0, "c16_32x32_k3", 1, 16, 32, 16, 3, 1, 1)]
+    if cfg in (2, 3):
+        n = 1 if cfg == 2 else 32
+        out = [
+            _mk(cfg, 0, "res64_56x56_k3", n, 64, 56, 64, 3, 1, 1),
+            _mk(cfg, 1, "res128_28x28_k3", n, 128, 28, 128, 3, 1, 1),
+            _mk(cfg, 2, "res256_14x14_k3", n, 256, 14, 256, 3, 1, 1),
+            _mk(cfg, 3, "res512_7x7_k3", n, 512, 7, 512, 3, 1, 1),
+        ]
+        if cfg == 2:
+            out += [
+                _mk(cfg, 4, "res64to128_56x56_k3s2", n, 64, 56, 128, 3, 2, 1),
+                _mk(cfg, 5, "res128to256_28x28_k3s2", n, 128, 28, 256, 3, 2, 1),
+                _mk(cfg, 6, "res256to512_14x14_k3s2", n, 256, 14, 512, 3, 2, 1),
+            ]
+        return out
+    if cfg == 4:
+        shapes = [(32, 64, 112), (64, 128, 56), (128, 256, 28), (256, 512, 14), (512, 1024, 7), (1024, 1024, 7)]
+        return [_mk(4, i, f"pw{c}to{k}_{hw}x{hw}", 16, c, hw, k, 1, 1, 0, (0.0, 1.0))
+                for i, (c, k, hw) in enumerate(shapes)]
+    if cfg == 5:
+        return [
+            _mk(5, 0, "mix256_128x128_k3", 16, 256, 128, 256, 3, 1, 1),
+            _mk(5, 1, "mix128_64x64_k5", 16, 128, 64, 128, 5, 1, 2),
+            _mk(5, 2, "mix64_112x112_k7", 16, 64, 112, 64, 7, 1, 3),
+        ]
+    raise ValueError(f"unknown workload config {cfg}")
+
+
+CONFIG_TITLES: Dict[int, str] = {
+    1: "cfg1: single 3x3 conv 16->16 32x32 N=1",
+    2: "cfg2: ResNet-18-style 3x3 layers N=1 (+stride-2 transitions)",
+    3: "cfg3: ResNet-18-style 3x3 stride-1 layers N=32",
+    4: "cfg4: MobileNet-v1-style pointwise 1x1 layers N=16",
+    5: "cfg5: mixed-kernel stress 3x3/5x5/7x7 N=16",
+}
+
+
+def small_parity_layers() -> List[ConvLayer]:
+    """Small ragged / edge layers the oracle finishes in well under a second each."""
+    def L(i, name, n, c, h, w, k, kh, kw, s=1, p=0, d=1):
+        return ConvLayer(name, n, c, h, w, k, kh, kw, s, p, d, (-1.0, 1.0), BASE_SEED + 9000 + i)
+    return [
+        L(0, "tiny_3x3", 1, 3, 6, 6, 2, 3, 3, 1, 1),
+        L(1, "ragged_7x7_k3", 2, 5, 7, 7, 6, 3, 3, 1, 1),
+        L(2, "ragged_14x9_k3", 3, 17, 14, 9, 33, 3, 3, 1, 1),
+        L(3, "nopad_13x13_k3", 2, 8, 13, 13, 8, 3, 3, 1, 0),
+        L(4, "k5_same_11x15", 2, 9, 11, 15, 7, 5, 5, 1, 2),
+        L(5, "k7_same_16x16", 1, 4, 16, 16, 5, 7, 7, 1, 3),
+        L(6, "k2_nopad_9x9", 2, 6, 9, 9, 4, 2, 2, 1, 0),
+        L(7, "stride2_k3", 2, 12, 15, 15, 10, 3, 3, 2, 1),
+        L(8, "dil2_k3", 1, 7, 12, 12, 9, 3, 3, 1, 2, 2),
+        L(9, "pw_1x1_odd", 3, 19, 7, 7, 21, 1, 1, 1, 0),
+        L(10, "pw_1x1_wide", 2, 40, 12, 12, 70, 1, 1, 1, 0),
+        L(11, "multi_tile_k3", 2, 70, 30, 34, 130, 3, 3, 1, 1),
+        L(12, "rect_1x7", 1, 5, 9, 20, 6, 1, 7, 1, 0),
+        L(13, "pad_bigger_than_needed", 1, 4, 8, 8, 4, 3, 3, 1, 2),
+    ]
