@@ -1,0 +1,213 @@
+/*
+ * mnn_conv.h -- C ABI of the MI355X (gfx950) convolution library.
+ *
+ * The library implements the data-parallel hot path of the MNN paper
+ * (arXiv 2002.12418):
+ *   - pre-inference scheme selection per layer shape        (Section 3.2)
+ *   - Winograd convolution F(n x n, k x k) with generated
+ *     transform matrices                                    (Section 3.3.1)
+ *   - k = 1 convolution as one large matrix multiplication  (Sections 3.2 (1), 3.3.2)
+ *   - sliding-window (direct) convolution as the fallback   (Section 3.2 (1))
+ *
+ * Conventions
+ *   - Every function returns MNN_OK (0) or a negative mnn_status; nothing is
+ *     thrown across the boundary.  mnn_last_error() gives a thread-local
+ *     message for the last failure on the calling thread.
+ *   - "device" pointers are HIP device addresses on the current device,
+ *     "host" pointers are ordinary process memory.  Tensors are float32,
+ *     dense, NCHW (input x[N][C][H][W], output y[N][K][H_o][W_o]) and KCRS
+ *     (weight w[K][C][kh][kw]); groups = 1.
+ *   - H_o = floor((H + 2*pad_h - dil_h*(kh-1) - 1)/stride_h) + 1, W_o alike;
+ *     the operation is a cross-correlation with zero padding plus bias.
+ *   - Streams are hipStream_t passed as void* (NULL = the default stream).
+ *   - A plan owns its workspace; mnn_conv_run allocates nothing and never
+ *     synchronises the host (preparation-execution decoupling, Section 3.2).
+ *     One plan must not be used from two streams at the same time.
+ */
+#ifndef MNN_CONV_H
+#define MNN_CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MNN_OK = 0,
+    MNN_E_INVALID_ARG = -1,   /* NULL pointer, non-positive size, empty output ...        */
+    MNN_E_UNSUPPORTED = -2,   /* valid request the library does not implement             */
+    MNN_E_HIP = -3,           /* a HIP runtime call failed (message holds hipGetErrorString) */
+    MNN_E_OOM = -4,           /* device allocation failed                                 */
+    MNN_E_NO_DEVICE = -5      /* no usable GPU in this process                            */
+} mnn_status;
+
+/* Layer shape: x[n][c_in][h][w] (*) w[c_out][c_in][kh][kw]. */
+typedef struct { int32_t n, c_in, h, w, c_out, kh, kw; } mnn_conv_shape;
+typedef struct { int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w; } mnn_conv_geom;
+
+/* The scheme pool of Section 3.2 (1). */
+typedef enum {
+    MNN_SCHEME_AUTO = 0,      /* let the planner decide (only meaningful in options)      */
+    MNN_SCHEME_DIRECT = 1,    /* sliding window                                           */
+    MNN_SCHEME_WINOGRAD = 2,  /* F(tile_n x tile_n, k x k)                                */
+    MNN_SCHEME_GEMM1X1 = 3    /* k = 1, stride 1, pad 0: one matrix multiplication        */
+} mnn_scheme_kind;
+
+/* Operand precision of the matrix-multiplication stage (accumulation is always fp32). */
+typedef enum {
+    MNN_GEMM_FP32 = 0,        /* fp32 operands, v_mfma_f32_32x32x2_f32                    */
+    MNN_GEMM_BF16 = 1         /* bf16 operands (RNE), bf16 MFMA                           */
+} mnn_gemm_prec;
+
+typedef struct {
+    int32_t kind;             /* mnn_scheme_kind                                          */
+    int32_t tile_n;           /* n of F(n,k); 0 unless kind == MNN_SCHEME_WINOGRAD        */
+    int32_t prec;             /* mnn_gemm_prec                                            */
+    float   est_ms;           /* time measured by the planner; < 0 when it was not timed  */
+} mnn_scheme;
+
+typedef struct {
+    int32_t force_kind;       /* MNN_SCHEME_AUTO or the scheme to use without timing      */
+    int32_t force_tile_n;     /* with force_kind == WINOGRAD: the n to use (0 = analytic) */
+    int32_t force_prec;       /* mnn_gemm_prec used for forced schemes                    */
+    int32_t allow_bf16;       /* 1: AUTO may also time bf16 candidates                    */
+    int32_t alpha_max;        /* largest n + k - 1 the planner may generate (default 8, max 12) */
+    float   point_scale_f;    /* f of the Winograd generator (default 0.5)                */
+    int32_t plan_warmup;      /* untimed launches per candidate (default 2)               */
+    int32_t plan_iters;       /* timed launches per candidate (default 10)                */
+    int32_t use_cache;        /* 1 (default): consult / fill the process-wide choice cache */
+} mnn_conv_options;
+
+typedef struct mnn_conv_plan_s* mnn_conv_plan_t;
+
+/* Stages of a plan, for per-stage timing and inspection. */
+enum {
+    MNN_STAGE_FILTER = 0,     /* weight preparation: G w G^T (Winograd) or transposition  */
+    MNN_STAGE_INPUT = 1,      /* B^T d B over all tiles                                   */
+    MNN_STAGE_GEMM = 2,       /* matrix multiplication (or the whole direct / 1x1 kernel) */
+    MNN_STAGE_OUTPUT = 3,     /* A^T m A + bias                                           */
+    MNN_STAGE_COUNT = 4
+};
+
+/* Plan buffers that tests may look at (device memory owned by the plan). */
+enum {
+    MNN_BUF_U = 0,            /* prepared weights.  Winograd: [alpha^2][C][ldk] (ldk = c_out rounded up to 4),
+                                 element (xi, c, k) = (G w[k][c] G^T)[xi / alpha][xi % alpha]        */
+    MNN_BUF_V = 1,            /* transformed input tiles  [alpha^2][C][ldp]  (ldp = P rounded up to 4) */
+    MNN_BUF_M = 2             /* products                 [alpha^2][c_out][ldp]                      */
+};
+
+typedef struct {
+    int32_t alpha, tile_n, tiles_h, tiles_w;  /* Winograd geometry (0 for other schemes)  */
+    int32_t p;                /* number of tiles N * tiles_h * tiles_w                    */
+    int32_t ldp, ldk;         /* leading dimensions of V/M rows and of U rows             */
+    int32_t h_out, w_out;
+} mnn_plan_info;
+
+/* Fills *opt with the defaults listed above.  Host. */
+int mnn_conv_options_default(mnn_conv_options* opt);
+
+/*
+ * Pre-inference for one layer (Section 3.2): validates the shape, enumerates the
+ * candidate schemes (k = 1, stride 1, pad 0 -> GEMM; stride or dilation != 1 or a
+ * non-square kernel -> sliding window only; otherwise sliding window and every
+ * F(n,k) with n >= 2 and n + k - 1 <= alpha_max), and unless a scheme is forced
+ * or cached, times every candidate on the device with scratch tensors and
+ * keeps the fastest (ties: smaller alpha).  Allocates the chosen scheme's
+ * workspace.  `stream` is used for the timing launches and is synchronised.
+ * shape, geom: host, read only.  options: host or NULL for defaults.
+ * *out_plan is set only on success; release it with mnn_conv_plan_destroy.
+ */
+int mnn_conv_plan(const mnn_conv_shape* shape, const mnn_conv_geom* geom,
+                  const mnn_conv_options* options, void* stream, mnn_conv_plan_t* out_plan);
+
+/* The scheme the plan runs.  Host. */
+int mnn_conv_plan_scheme(mnn_conv_plan_t plan, mnn_scheme* out);
+
+/* All schemes the planner considered, timed ones carrying est_ms >= 0.  Writes at
+ * most `cap` entries to out (may be NULL with cap 0) and the total to *count.  Host. */
+int mnn_conv_plan_candidates(mnn_conv_plan_t plan, mnn_scheme* out, int32_t cap, int32_t* count);
+
+/* Geometry of the plan.  Host. */
+int mnn_conv_plan_info(mnn_conv_plan_t plan, mnn_plan_info* out);
+
+/* Bytes of device memory the plan owns (workspace + prepared weights). */
+size_t mnn_conv_workspace_bytes(mnn_conv_plan_t plan);
+
+/*
+ * Inference for one layer: enqueues the plan's kernels on `stream`.
+ * input, weight, bias (may be NULL), output: device, float32, layouts above;
+ * input/weight/bias are read only, output is overwritten.  The prepared
+ * weights (Winograd: U = G w G^T, Section 3.3.1) are rebuilt only when `weight`
+ * differs from the pointer of the previous call or after
+ * mnn_conv_invalidate_weights; otherwise the call launches only the
+ * per-inference stages.  Returns MNN_E_HIP if a launch fails.
+ */
+int mnn_conv_run(mnn_conv_plan_t plan, const float* input, const float* weight,
+                 const float* bias, float* output, void* stream);
+
+/* Same work as mnn_conv_run repeated `iters` times with HIP events around each
+ * stage; synchronises `stream` and writes the mean milliseconds per stage to
+ * stage_ms[MNN_STAGE_COUNT] (host; stages the scheme does not have get 0;
+ * MNN_STAGE_FILTER is run and timed every iteration here). */
+int mnn_conv_run_timed(mnn_conv_plan_t plan, const float* input, const float* weight,
+                       const float* bias, float* output, void* stream, int32_t iters,
+                       float* stage_ms);
+
+/* Runs a single stage (MNN_STAGE_*) of the plan; the stages before it must have
+ * run with the same tensors.  For per-kernel profiling. */
+int mnn_conv_run_stage(mnn_conv_plan_t plan, int32_t stage, const float* input, const float* weight,
+                       const float* bias, float* output, void* stream);
+
+/* Forces the weight preparation to run again on the next mnn_conv_run. */
+int mnn_conv_invalidate_weights(mnn_conv_plan_t plan);
+
+/* Device address and size in bytes of one of the plan's buffers (MNN_BUF_*);
+ * *ptr is NULL when the scheme has no such buffer. */
+int mnn_conv_plan_buffer(mnn_conv_plan_t plan, int32_t which, void** ptr, size_t* bytes);
+
+void mnn_conv_plan_destroy(mnn_conv_plan_t plan);
+
+/*
+ * Winograd generator (Section 3.3.1 (3)).  Host only.  Interpolation points are
+ * 0, +f, -f, +2f, -2f, ... (the first n + k - 2 of them) and infinity.  Writes
+ * row-major AT[n][alpha], G[alpha][k], BT[alpha][alpha], alpha = n + k - 1, such
+ * that  AT [ (G g) (.) (BT d) ]_i = sum_j d[i+j] g[j].
+ */
+int mnn_conv_get_transforms(int32_t n, int32_t k, float f, float* AT, float* G, float* BT);
+
+/*
+ * Analytic cost of Section 3.2 (1).  Host only.
+ * mnn_conv_analytic_cost: cost of the whole output plane with output tile n,
+ *   ceil(o_h/n) * ceil(o_w/n) * [2 i_c a^3 + i_c o_c a^2 + n a (2n + k - 1)], a = n + k - 1.
+ * mnn_conv_analytic_tile: the n in [1, alpha_max - k + 1] with the least such cost
+ *   (1 means sliding window); ties go to the smaller n.
+ */
+int mnn_conv_analytic_cost(int32_t k, int32_t i_c, int32_t o_c, int32_t o_h, int32_t o_w,
+                           int32_t n, double* cost);
+int mnn_conv_analytic_tile(int32_t k, int32_t i_c, int32_t o_c, int32_t o_h, int32_t o_w,
+                           int32_t alpha_max, int32_t* n_hat);
+
+/* The candidate list mnn_conv_plan would time for this layer, without touching
+ * the device.  Host only.  Same cap / count convention as above. */
+int mnn_conv_enumerate(const mnn_conv_shape* shape, const mnn_conv_geom* geom,
+                       const mnn_conv_options* options, mnn_scheme* out, int32_t cap, int32_t* count);
+
+/* Index of the candidate the planner keeps given measured times (est_ms):
+ * the least est_ms; among times within 2 % of it, the smallest alpha, then the
+ * fp32 variant.  Candidates with est_ms < 0 are ignored.  Host only. */
+int mnn_conv_select(const mnn_scheme* cands, int32_t count, int32_t k, int32_t* chosen);
+
+/* Process-wide cache of planner choices keyed by device, shape, geometry and options. */
+int mnn_conv_cache_size(void);
+void mnn_conv_cache_clear(void);
+
+const char* mnn_last_error(void);
+int mnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MNN_CONV_H */

@@ -1,0 +1,326 @@
+"""ctypes binding of include/mnn_conv.h.  Argument marshalling only.
+
+PyTorch is used for device memory and streams: tensors are passed as raw
+``data_ptr()`` addresses and the current stream as its ``hipStream_t`` handle.
+There is no CPU fallback: if libmnnconv.so is missing the import fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_double, c_float, c_int32, c_size_t, c_void_p
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libmnnconv.so")
+
+SCHEME_AUTO, SCHEME_DIRECT, SCHEME_WINOGRAD, SCHEME_GEMM1X1 = 0, 1, 2, 3
+GEMM_FP32, GEMM_BF16 = 0, 1
+STAGE_FILTER, STAGE_INPUT, STAGE_GEMM, STAGE_OUTPUT, STAGE_COUNT = 0, 1, 2, 3, 4
+BUF_U, BUF_V, BUF_M = 0, 1, 2
+_KIND_NAMES = {SCHEME_AUTO: "auto", SCHEME_DIRECT: "direct", SCHEME_WINOGRAD: "winograd", SCHEME_GEMM1X1: "gemm1x1"}
+
+
+class MnnError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"mnn_conv error {code}: {msg}")
+        self.code = code
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [(n, c_int32) for n in ("n", "c_in", "h", "w", "c_out", "kh", "kw")]
+
+
+class _Geom(ctypes.Structure):
+    _fields_ = [(n, c_int32) for n in ("stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w")]
+
+
+class _Scheme(ctypes.Structure):
+    _fields_ = [("kind", c_int32), ("tile_n", c_int32), ("prec", c_int32), ("est_ms", c_float)]
+
+
+class _Options(ctypes.Structure):
+    _fields_ = [("force_kind", c_int32), ("force_tile_n", c_int32), ("force_prec", c_int32),
+                ("allow_bf16", c_int32), ("alpha_max", c_int32), ("point_scale_f", c_float),
+                ("plan_warmup", c_int32), ("plan_iters", c_int32), ("use_cache", c_int32)]
+
+
+class _Info(ctypes.Structure):
+    _fields_ = [(n, c_int32) for n in ("alpha", "tile_n", "tiles_h", "tiles_w", "p", "ldp", "ldk", "h_out", "w_out")]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        # build once if nothing is built; a missing toolchain is a hard error
+        from .build import build_library
+        build_library(verbose=False)
+    # torch first: its bundled HIP runtime must be the one libmnnconv.so binds to,
+    # otherwise device pointers from torch would belong to a different runtime instance.
+    import torch  # noqa: F401
+    L = ctypes.CDLL(_LIB_PATH)
+    vp = c_void_p
+    L.mnn_conv_options_default.argtypes = [POINTER(_Options)]
+    L.mnn_conv_plan.argtypes = [POINTER(_Shape), POINTER(_Geom), POINTER(_Options), vp, POINTER(vp)]
+    L.mnn_conv_plan_scheme.argtypes = [vp, POINTER(_Scheme)]
+    L.mnn_conv_plan_candidates.argtypes = [vp, POINTER(_Scheme), c_int32, POINTER(c_int32)]
+    L.mnn_conv_plan_info.argtypes = [vp, POINTER(_Info)]
+    L.mnn_conv_workspace_bytes.argtypes = [vp]
+    L.mnn_conv_workspace_bytes.restype = c_size_t
+    L.mnn_conv_run.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.mnn_conv_run_timed.argtypes = [vp, vp, vp, vp, vp, vp, c_int32, POINTER(c_float)]
+    L.mnn_conv_run_stage.argtypes = [vp, c_int32, vp, vp, vp, vp, vp]
+    L.mnn_conv_invalidate_weights.argtypes = [vp]
+    L.mnn_conv_plan_buffer.argtypes = [vp, c_int32, POINTER(vp), POINTER(c_size_t)]
+    L.mnn_conv_plan_destroy.argtypes = [vp]
+    L.mnn_conv_plan_destroy.restype = None
+    L.mnn_conv_get_transforms.argtypes = [c_int32, c_int32, c_float, vp, vp, vp]
+    L.mnn_conv_analytic_cost.argtypes = [c_int32] * 6 + [POINTER(c_double)]
+    L.mnn_conv_analytic_tile.argtypes = [c_int32] * 6 + [POINTER(c_int32)]
+    L.mnn_conv_enumerate.argtypes = [POINTER(_Shape), POINTER(_Geom), POINTER(_Options), POINTER(_Scheme), c_int32,
+                                     POINTER(c_int32)]
+    L.mnn_conv_select.argtypes = [POINTER(_Scheme), c_int32, c_int32, POINTER(c_int32)]
+    L.mnn_conv_cache_size.argtypes = []
+    L.mnn_conv_cache_clear.argtypes = []
+    L.mnn_conv_cache_clear.restype = None
+    L.mnn_last_error.restype = c_char_p
+    L.mnn_version.argtypes = []
+    return L
+
+
+lib = _load()
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise MnnError(rc, (lib.mnn_last_error() or b"").decode("utf-8", "replace"))
+
+
+def version() -> int:
+    return int(lib.mnn_version())
+
+
+@dataclass
+class Scheme:
+    kind: int
+    tile_n: int = 0
+    prec: int = GEMM_FP32
+    est_ms: float = -1.0
+
+    def label(self, k: Optional[int] = None) -> str:
+        p = "" if self.prec == GEMM_FP32 else "/bf16"
+        if self.kind == SCHEME_WINOGRAD:
+            return f"F({self.tile_n},{k if k is not None else 'k'}){p}"
+        return _KIND_NAMES.get(self.kind, str(self.kind)) + p
+
+    def _c(self) -> _Scheme:
+        return _Scheme(self.kind, self.tile_n, self.prec, self.est_ms)
+
+    @staticmethod
+    def _from(c: _Scheme) -> "Scheme":
+        return Scheme(int(c.kind), int(c.tile_n), int(c.prec), float(c.est_ms))
+
+
+@dataclass
+class Options:
+    force_kind: int = SCHEME_AUTO
+    force_tile_n: int = 0
+    force_prec: int = GEMM_FP32
+    allow_bf16: int = 0
+    alpha_max: int = 8
+    point_scale_f: float = 0.5
+    plan_warmup: int = 2
+    plan_iters: int = 10
+    use_cache: int = 1
+
+    def _c(self) -> _Options:
+        return _Options(self.force_kind, self.force_tile_n, self.force_prec, self.allow_bf16, self.alpha_max,
+                        self.point_scale_f, self.plan_warmup, self.plan_iters, self.use_cache)
+
+    @staticmethod
+    def defaults() -> "Options":
+        c = _Options()
+        _check(lib.mnn_conv_options_default(byref(c)))
+        return Options(*(getattr(c, f) for f, _ in _Options._fields_))
+
+
+def _pair(v) -> Tuple[int, int]:
+    if isinstance(v, (tuple, list)):
+        return int(v[0]), int(v[1])
+    return int(v), int(v)
+
+
+def _shape_geom(n, c_in, h, w, c_out, kh, kw, stride, pad, dil):
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    dh, dw = _pair(dil)
+    return _Shape(n, c_in, h, w, c_out, kh, kw), _Geom(sh, sw, ph, pw, dh, dw)
+
+
+def get_transforms(n: int, k: int, f: float = 0.5):
+    """(A^T [n, alpha], G [alpha, k], B^T [alpha, alpha]) as float32 arrays from the host generator."""
+    a = n + k - 1
+    AT = np.zeros((max(n, 1), max(a, 1)), np.float32)
+    G = np.zeros((max(a, 1), max(k, 1)), np.float32)
+    BT = np.zeros((max(a, 1), max(a, 1)), np.float32)
+    _check(lib.mnn_conv_get_transforms(n, k, f, AT.ctypes.data, G.ctypes.data, BT.ctypes.data))
+    return AT, G, BT
+
+
+def analytic_cost(k, i_c, o_c, o_h, o_w, n) -> float:
+    out = c_double()
+    _check(lib.mnn_conv_analytic_cost(k, i_c, o_c, o_h, o_w, n, byref(out)))
+    return float(out.value)
+
+
+def analytic_tile(k, i_c, o_c, o_h, o_w, alpha_max=8) -> int:
+    out = c_int32()
+    _check(lib.mnn_conv_analytic_tile(k, i_c, o_c, o_h, o_w, alpha_max, byref(out)))
+    return int(out.value)
+
+
+def enumerate_schemes(n, c_in, h, w, c_out, kh, kw, stride=1, pad=0, dil=1, options: Optional[Options] = None) -> List[Scheme]:
+    s, g = _shape_geom(n, c_in, h, w, c_out, kh, kw, stride, pad, dil)
+    o = options._c() if options else None
+    cnt = c_int32()
+    buf = (_Scheme * 64)()
+    _check(lib.mnn_conv_enumerate(byref(s), byref(g), byref(o) if o else None, buf, 64, byref(cnt)))
+    return [Scheme._from(buf[i]) for i in range(min(64, cnt.value))]
+
+
+def select_scheme(cands: Sequence[Scheme], k: int) -> int:
+    arr = (_Scheme * len(cands))(*[c._c() for c in cands])
+    out = c_int32()
+    _check(lib.mnn_conv_select(arr, len(cands), k, byref(out)))
+    return int(out.value)
+
+
+def cache_size() -> int:
+    return int(lib.mnn_conv_cache_size())
+
+
+def cache_clear() -> None:
+    lib.mnn_conv_cache_clear()
+
+
+def _stream_handle(stream) -> int:
+    import torch
+    if stream is None:
+        if not torch.cuda.is_available():
+            return 0          # the library itself reports MNN_E_NO_DEVICE
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+class ConvPlan:
+    """mnn_conv_plan / mnn_conv_run for one layer shape."""
+
+    def __init__(self, n, c_in, h, w, c_out, kh, kw, stride=1, pad=0, dil=1,
+                 options: Optional[Options] = None, stream=None):
+        self._h = c_void_p()
+        self.shape = (n, c_in, h, w, c_out, kh, kw)
+        s, g = _shape_geom(n, c_in, h, w, c_out, kh, kw, stride, pad, dil)
+        o = options._c() if options else None
+        _check(lib.mnn_conv_plan(byref(s), byref(g), byref(o) if o else None, _stream_handle(stream), byref(self._h)))
+        info = _Info()
+        _check(lib.mnn_conv_plan_info(self._h, byref(info)))
+        self.info = {f: int(getattr(info, f)) for f, _ in _Info._fields_}
+        self.out_shape = (n, c_out, self.info["h_out"], self.info["w_out"])
+
+    @classmethod
+    def for_layer(cls, layer, options: Optional[Options] = None, stream=None) -> "ConvPlan":
+        return cls(layer.n, layer.c_in, layer.h, layer.w, layer.c_out, layer.kh, layer.kw,
+                   stride=layer.stride, pad=layer.pad, dil=layer.dil, options=options, stream=stream)
+
+    @property
+    def scheme(self) -> Scheme:
+        c = _Scheme()
+        _check(lib.mnn_conv_plan_scheme(self._h, byref(c)))
+        return Scheme._from(c)
+
+    @property
+    def candidates(self) -> List[Scheme]:
+        cnt = c_int32()
+        buf = (_Scheme * 64)()
+        _check(lib.mnn_conv_plan_candidates(self._h, buf, 64, byref(cnt)))
+        return [Scheme._from(buf[i]) for i in range(min(64, cnt.value))]
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib.mnn_conv_workspace_bytes(self._h))
+
+    def _check_tensors(self, x, w, b, y):
+        import torch
+        n, c_in, h, wd, c_out, kh, kw = self.shape
+        for t, shp, name in ((x, (n, c_in, h, wd), "input"), (w, (c_out, c_in, kh, kw), "weight"),
+                             (y, self.out_shape, "output")):
+            if tuple(t.shape) != tuple(shp) or t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError(f"{name}: expected contiguous float32 device tensor of shape {shp}, got {tuple(t.shape)} {t.dtype}")
+        if b is not None and (tuple(b.shape) != (c_out,) or b.dtype != torch.float32 or not b.is_cuda or not b.is_contiguous()):
+            raise ValueError("bias: expected contiguous float32 device tensor of shape (c_out,)")
+
+    def run(self, x, w, b, y=None, stream=None):
+        import torch
+        if y is None:
+            y = torch.empty(self.out_shape, dtype=torch.float32, device=x.device)
+        self._check_tensors(x, w, b, y)
+        _check(lib.mnn_conv_run(self._h, x.data_ptr(), w.data_ptr(), b.data_ptr() if b is not None else None,
+                                y.data_ptr(), _stream_handle(stream)))
+        return y
+
+    def run_stage(self, stage: int, x, w, b, y, stream=None):
+        self._check_tensors(x, w, b, y)
+        _check(lib.mnn_conv_run_stage(self._h, stage, x.data_ptr(), w.data_ptr(),
+                                      b.data_ptr() if b is not None else None, y.data_ptr(), _stream_handle(stream)))
+
+    def run_timed(self, x, w, b, y, iters: int = 10, stream=None) -> List[float]:
+        self._check_tensors(x, w, b, y)
+        ms = (c_float * STAGE_COUNT)()
+        _check(lib.mnn_conv_run_timed(self._h, x.data_ptr(), w.data_ptr(), b.data_ptr() if b is not None else None,
+                                      y.data_ptr(), _stream_handle(stream), iters, ms))
+        return [float(v) for v in ms]
+
+    def invalidate_weights(self):
+        _check(lib.mnn_conv_invalidate_weights(self._h))
+
+    def buffer(self, which: int) -> Tuple[int, int]:
+        p, nbytes = c_void_p(), c_size_t()
+        _check(lib.mnn_conv_plan_buffer(self._h, which, byref(p), byref(nbytes)))
+        return (p.value or 0), int(nbytes.value)
+
+    def buffer_to_numpy(self, which: int) -> Optional[np.ndarray]:
+        """Copy one of the plan's device buffers to the host as a flat float32 array (test helper)."""
+        import torch
+        ptr, nbytes = self.buffer(which)
+        if not ptr:
+            return None
+        torch.cuda.synchronize()
+        out = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda")
+        rc = torch.cuda.cudart().cudaMemcpy(out.data_ptr(), ptr, nbytes, 3)  # device-to-device
+        if int(rc) != 0:
+            raise RuntimeError(f"memcpy of plan buffer failed ({rc})")
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib.mnn_conv_plan_destroy(self._h)
+            self._h = c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

@@ -1,0 +1,710 @@
+// C ABI, plan objects and the pre-inference planner (Section 3.2 of the MNN
+// paper: computation scheme selection + preparation-execution decoupling).
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <new>
+#include <string>
+#include <tuple>
+#include <vector>
+
+#include "../../include/mnn_conv.h"
+#include "cook_toom_gen.hpp"
+#include "kernels.hpp"
+
+using namespace mnnconv;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+int fail_hip(hipError_t e, const char* what)
+{
+    // hipGetLastError clears the sticky error so that one failure is not reported twice
+    (void)hipGetLastError();
+    if (e == hipErrorOutOfMemory) return fail(MNN_E_OOM, "%s: %s", what, hipGetErrorString(e));
+    return fail(MNN_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+void default_options(mnn_conv_options* o)
+{
+    o->force_kind = MNN_SCHEME_AUTO;
+    o->force_tile_n = 0;
+    o->force_prec = MNN_GEMM_FP32;
+    o->allow_bf16 = 0;
+    o->alpha_max = 8;
+    o->point_scale_f = 0.5f;
+    o->plan_warmup = 2;
+    o->plan_iters = 10;
+    o->use_cache = 1;
+}
+
+struct Layer {
+    mnn_conv_shape s;
+    mnn_conv_geom g;
+    int Ho, Wo;
+};
+
+int validate(const mnn_conv_shape* shape, const mnn_conv_geom* geom, Layer* L)
+{
+    if (!shape || !geom) return fail(MNN_E_INVALID_ARG, "shape and geom must not be NULL");
+    const mnn_conv_shape& s = *shape;
+    const mnn_conv_geom& g = *geom;
+    if (s.n <= 0 || s.c_in <= 0 || s.h <= 0 || s.w <= 0 || s.c_out <= 0 || s.kh <= 0 || s.kw <= 0)
+        return fail(MNN_E_INVALID_ARG, "all shape entries must be positive");
+    if (g.stride_h <= 0 || g.stride_w <= 0 || g.dil_h <= 0 || g.dil_w <= 0 || g.pad_h < 0 || g.pad_w < 0)
+        return fail(MNN_E_INVALID_ARG, "stride and dilation must be positive, padding non-negative");
+    const long long eh = (long long)s.h + 2ll * g.pad_h - (long long)g.dil_h * (s.kh - 1) - 1;
+    const long long ew = (long long)s.w + 2ll * g.pad_w - (long long)g.dil_w * (s.kw - 1) - 1;
+    if (eh < 0 || ew < 0) return fail(MNN_E_INVALID_ARG, "kernel extent exceeds the padded input: empty output");
+    L->s = s;
+    L->g = g;
+    L->Ho = (int)(eh / g.stride_h) + 1;
+    L->Wo = (int)(ew / g.stride_w) + 1;
+    const long long in_elems = (long long)s.n * s.c_in * s.h * s.w;
+    const long long out_elems = (long long)s.n * s.c_out * L->Ho * L->Wo;
+    const long long w_elems = (long long)s.c_out * s.c_in * s.kh * s.kw;
+    if (in_elems >= (1ll << 40) || out_elems >= (1ll << 40) || w_elems >= (1ll << 31))
+        return fail(MNN_E_UNSUPPORTED, "tensor too large");
+    return MNN_OK;
+}
+
+int validate_options(const mnn_conv_options* in, mnn_conv_options* o)
+{
+    if (in) *o = *in; else default_options(o);
+    if (o->alpha_max <= 0) o->alpha_max = 8;
+    if (o->alpha_max > kMaxAlpha) return fail(MNN_E_UNSUPPORTED, "alpha_max above %d", kMaxAlpha);
+    if (!(o->point_scale_f > 0.f)) return fail(MNN_E_INVALID_ARG, "point_scale_f must be positive");
+    if (o->plan_warmup < 0 || o->plan_iters <= 0) return fail(MNN_E_INVALID_ARG, "plan_warmup >= 0 and plan_iters > 0 required");
+    if (o->force_kind < MNN_SCHEME_AUTO || o->force_kind > MNN_SCHEME_GEMM1X1)
+        return fail(MNN_E_INVALID_ARG, "unknown force_kind %d", o->force_kind);
+    if (o->force_prec != MNN_GEMM_FP32 && o->force_prec != MNN_GEMM_BF16)
+        return fail(MNN_E_INVALID_ARG, "unknown force_prec %d", o->force_prec);
+    return MNN_OK;
+}
+
+bool is_pointwise(const Layer& L)
+{
+    return L.s.kh == 1 && L.s.kw == 1 && L.g.stride_h == 1 && L.g.stride_w == 1 && L.g.pad_h == 0 && L.g.pad_w == 0;
+}
+
+bool winograd_admissible(const Layer& L)
+{
+    return L.s.kh == L.s.kw && L.s.kh >= 2 && L.g.stride_h == 1 && L.g.stride_w == 1 && L.g.dil_h == 1 &&
+           L.g.dil_w == 1;
+}
+
+mnn_scheme make_scheme(int kind, int n, int prec)
+{
+    mnn_scheme s;
+    s.kind = kind; s.tile_n = n; s.prec = prec; s.est_ms = -1.f;
+    return s;
+}
+
+// Section 3.2 (1): k = 1 -> matrix multiplication; k > 1 -> sliding window or F(n,k).
+std::vector<mnn_scheme> enumerate(const Layer& L, const mnn_conv_options& o)
+{
+    std::vector<mnn_scheme> out;
+    if (is_pointwise(L)) {
+        out.push_back(make_scheme(MNN_SCHEME_GEMM1X1, 0, MNN_GEMM_FP32));
+        return out;
+    }
+    out.push_back(make_scheme(MNN_SCHEME_DIRECT, 0, MNN_GEMM_FP32));
+    if (winograd_admissible(L)) {
+        const int k = L.s.kh;
+        for (int n = 2; n + k - 1 <= o.alpha_max; ++n)
+            if (winograd_kernels_available(n, k)) out.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, MNN_GEMM_FP32));
+    }
+    return out;
+}
+
+double analytic_cost(int k, int ic, int oc, int oh, int ow, int n)
+{
+    const double a = n + k - 1;
+    const double blocks = (double)((oh + n - 1) / n) * (double)((ow + n - 1) / n);
+    return blocks * (2.0 * ic * a * a * a + (double)ic * oc * a * a + (double)n * a * (2.0 * n + k - 1));
+}
+
+int analytic_tile(int k, int ic, int oc, int oh, int ow, int alpha_max)
+{
+    int best = 1;
+    double bc = analytic_cost(k, ic, oc, oh, ow, 1);
+    for (int n = 2; n + k - 1 <= alpha_max; ++n) {
+        const double c = analytic_cost(k, ic, oc, oh, ow, n);
+        if (c < bc) { bc = c; best = n; }
+    }
+    return best;
+}
+
+int select_scheme(const mnn_scheme* c, int count, int k)
+{
+    int best = -1;
+    for (int i = 0; i < count; ++i)
+        if (c[i].est_ms >= 0.f && (best < 0 || c[i].est_ms < c[best].est_ms)) best = i;
+    if (best < 0) return -1;
+    const float limit = c[best].est_ms * 1.02f;
+    auto alpha_of = [k](const mnn_scheme& s) { return s.kind == MNN_SCHEME_WINOGRAD ? s.tile_n + k - 1 : k; };
+    int pick = -1;
+    for (int i = 0; i < count; ++i) {
+        if (c[i].est_ms < 0.f || c[i].est_ms > limit) continue;
+        if (pick < 0) { pick = i; continue; }
+        const auto ki = std::make_tuple(alpha_of(c[i]), c[i].prec, c[i].est_ms);
+        const auto kp = std::make_tuple(alpha_of(c[pick]), c[pick].prec, c[pick].est_ms);
+        if (ki < kp) pick = i;
+    }
+    return pick;
+}
+
+// ------------------------------------------------------------------ one realised scheme
+struct Impl {
+    mnn_scheme scheme{};
+    Layer L{};
+    WinogradMatrices mats;
+    WinoGeom wg{};
+    DirectGeom dg{};
+    float* U = nullptr; size_t U_bytes = 0;
+    float* V = nullptr; size_t V_bytes = 0;
+    float* M = nullptr; size_t M_bytes = 0;
+    int ldk = 0;
+
+    ~Impl() { release(); }
+    Impl() = default;
+    Impl(const Impl&) = delete;
+    Impl& operator=(const Impl&) = delete;
+
+    void release()
+    {
+        if (U) (void)hipFree(U);
+        if (V) (void)hipFree(V);
+        if (M) (void)hipFree(M);
+        U = V = M = nullptr;
+        U_bytes = V_bytes = M_bytes = 0;
+    }
+
+    int alloc_zero(float** p, size_t bytes, const char* what)
+    {
+        hipError_t e = hipMalloc((void**)p, bytes);
+        if (e != hipSuccess) { *p = nullptr; return fail_hip(e, what); }
+        e = hipMemset(*p, 0, bytes);
+        if (e != hipSuccess) return fail_hip(e, what);
+        // plan time: make the cleared padding visible to whatever stream runs the plan later
+        e = hipDeviceSynchronize();
+        if (e != hipSuccess) return fail_hip(e, what);
+        return MNN_OK;
+    }
+
+    int prepare(const Layer& layer, const mnn_scheme& s, const mnn_conv_options& o)
+    {
+        L = layer;
+        scheme = s;
+        const mnn_conv_shape& sh = L.s;
+        ldk = round_up(sh.c_out, 4);
+        if (s.prec != MNN_GEMM_FP32) return fail(MNN_E_UNSUPPORTED, "bf16 GEMM is not built into this library yet");
+        if (s.kind == MNN_SCHEME_WINOGRAD) {
+            if (!winograd_admissible(L)) return fail(MNN_E_UNSUPPORTED, "Winograd needs a square kernel >= 2, stride 1, dilation 1");
+            const int n = s.tile_n, k = sh.kh;
+            if (!winograd_kernels_available(n, k) || n + k - 1 > kMaxAlpha)
+                return fail(MNN_E_UNSUPPORTED, "F(%d,%d) is outside the built range (n 2..8, k 2..7, alpha <= %d)", n, k, kMaxAlpha);
+            if (!generate_winograd(n, k, (double)o.point_scale_f, &mats))
+                return fail(MNN_E_UNSUPPORTED, "generator rejected F(%d,%d)", n, k);
+            wg.N = sh.n; wg.C = sh.c_in; wg.H = sh.h; wg.W = sh.w; wg.K = sh.c_out;
+            wg.Ho = L.Ho; wg.Wo = L.Wo; wg.pad_h = L.g.pad_h; wg.pad_w = L.g.pad_w;
+            wg.n = n; wg.k = k; wg.alpha = n + k - 1;
+            wg.th = (L.Ho + n - 1) / n; wg.tw = (L.Wo + n - 1) / n;
+            const long long P = (long long)sh.n * wg.th * wg.tw;
+            if (P >= (1ll << 30)) return fail(MNN_E_UNSUPPORTED, "too many tiles");
+            wg.P = (int)P; wg.ldp = round_up(wg.P, 4); wg.ldk = ldk;
+            const size_t a2 = (size_t)wg.alpha * wg.alpha;
+            if ((long long)wg.C * wg.ldp >= (1ll << 31) || (long long)wg.K * wg.ldp >= (1ll << 31))
+                return fail(MNN_E_UNSUPPORTED, "Winograd-domain plane too large");
+            U_bytes = a2 * sh.c_in * ldk * sizeof(float);
+            V_bytes = a2 * sh.c_in * wg.ldp * sizeof(float);
+            M_bytes = a2 * sh.c_out * wg.ldp * sizeof(float);
+            int rc;
+            if ((rc = alloc_zero(&U, U_bytes, "hipMalloc U"))) return rc;
+            if ((rc = alloc_zero(&V, V_bytes, "hipMalloc V"))) return rc;
+            if ((rc = alloc_zero(&M, M_bytes, "hipMalloc M"))) return rc;
+            return MNN_OK;
+        }
+        if (s.kind == MNN_SCHEME_GEMM1X1) {
+            if (!is_pointwise(L)) return fail(MNN_E_UNSUPPORTED, "GEMM scheme needs a 1x1 kernel, stride 1, no padding");
+            if ((long long)sh.n * sh.h * sh.w >= (1ll << 31)) return fail(MNN_E_UNSUPPORTED, "too many pixels");
+            U_bytes = (size_t)sh.c_in * ldk * sizeof(float);
+            return alloc_zero(&U, U_bytes, "hipMalloc Wt");
+        }
+        if (s.kind == MNN_SCHEME_DIRECT) {
+            dg.N = sh.n; dg.C = sh.c_in; dg.H = sh.h; dg.W = sh.w; dg.K = sh.c_out; dg.kh = sh.kh; dg.kw = sh.kw;
+            dg.Ho = L.Ho; dg.Wo = L.Wo;
+            dg.stride_h = L.g.stride_h; dg.stride_w = L.g.stride_w; dg.pad_h = L.g.pad_h; dg.pad_w = L.g.pad_w;
+            dg.dil_h = L.g.dil_h; dg.dil_w = L.g.dil_w;
+            return MNN_OK;
+        }
+        return fail(MNN_E_INVALID_ARG, "unknown scheme kind %d", s.kind);
+    }
+
+    bool has_stage(int st) const
+    {
+        switch (scheme.kind) {
+            case MNN_SCHEME_WINOGRAD: return true;
+            case MNN_SCHEME_GEMM1X1: return st == MNN_STAGE_FILTER || st == MNN_STAGE_GEMM;
+            default: return st == MNN_STAGE_GEMM;
+        }
+    }
+
+    int run_stage(int st, const float* x, const float* w, const float* b, float* y, hipStream_t s)
+    {
+        if (!has_stage(st)) return MNN_OK;
+        hipError_t e = hipSuccess;
+        const mnn_conv_shape& sh = L.s;
+        if (scheme.kind == MNN_SCHEME_WINOGRAD) {
+            switch (st) {
+                case MNN_STAGE_FILTER: e = launch_filter_transform(wg, mats.G.data(), w, U, s); break;
+                case MNN_STAGE_INPUT: e = launch_input_transform(wg, mats.BT.data(), x, V, s); break;
+                case MNN_STAGE_GEMM: {
+                    GemmProblem p{};
+                    p.At = U; p.B = V; p.D = M; p.bias = nullptr;
+                    p.M = wg.K; p.Ncols = wg.ldp; p.R = wg.C; p.batch = wg.alpha * wg.alpha;
+                    p.lda = ldk; p.L = wg.ldp;
+                    p.strideA_batch = (long long)wg.C * ldk;
+                    p.strideB_batch = (long long)wg.C * wg.ldp; p.strideB_img = 0; p.strideB_row = wg.ldp;
+                    p.strideD_batch = (long long)wg.K * wg.ldp; p.strideD_img = 0; p.strideD_row = wg.ldp;
+                    e = launch_gemm_f32(p, s);
+                    break;
+                }
+                case MNN_STAGE_OUTPUT: e = launch_output_transform(wg, mats.AT.data(), M, b, y, s); break;
+            }
+        } else if (scheme.kind == MNN_SCHEME_GEMM1X1) {
+            const int HW = sh.h * sh.w;
+            if (st == MNN_STAGE_FILTER) {
+                e = launch_weight_transpose(w, U, sh.c_out, sh.c_in, ldk, s);
+            } else {
+                GemmProblem p{};
+                p.At = U; p.B = x; p.D = y; p.bias = b;
+                p.M = sh.c_out; p.Ncols = sh.n * HW; p.R = sh.c_in; p.batch = 1;
+                p.lda = ldk; p.L = HW;
+                p.strideA_batch = 0;
+                p.strideB_batch = 0; p.strideB_img = (long long)sh.c_in * HW; p.strideB_row = HW;
+                p.strideD_batch = 0; p.strideD_img = (long long)sh.c_out * HW; p.strideD_row = HW;
+                e = launch_gemm_f32(p, s);
+            }
+        } else {
+            e = launch_direct_conv(dg, x, w, b, y, s);
+        }
+        if (e != hipSuccess) return fail_hip(e, "kernel launch");
+        return MNN_OK;
+    }
+
+    size_t bytes() const { return U_bytes + V_bytes + M_bytes; }
+};
+
+// ------------------------------------------------------------------ choice cache
+using CacheKey = std::tuple<int, std::vector<int>, float>;
+std::mutex g_cache_mu;
+std::map<CacheKey, mnn_scheme> g_cache;
+
+CacheKey cache_key(int device, const Layer& L, const mnn_conv_options& o)
+{
+    std::vector<int> v = {L.s.n, L.s.c_in, L.s.h, L.s.w, L.s.c_out, L.s.kh, L.s.kw,
+                          L.g.stride_h, L.g.stride_w, L.g.pad_h, L.g.pad_w, L.g.dil_h, L.g.dil_w,
+                          o.alpha_max, o.allow_bf16};
+    return CacheKey(device, v, o.point_scale_f);
+}
+
+}  // namespace
+
+struct mnn_conv_plan_s {
+    Layer L{};
+    mnn_conv_options opt{};
+    int device = 0;
+    Impl impl;
+    std::vector<mnn_scheme> cands;
+    const float* cached_weight = nullptr;
+    bool weights_valid = false;
+    bool from_cache = false;
+};
+
+namespace {
+
+struct Scratch {
+    float *x = nullptr, *w = nullptr, *y = nullptr;
+    ~Scratch()
+    {
+        if (x) (void)hipFree(x);
+        if (w) (void)hipFree(w);
+        if (y) (void)hipFree(y);
+    }
+};
+
+// Times one candidate: `warmup` untimed and `iters` timed passes of the
+// per-inference stages, bracketed by HIP events on `s`.
+int time_candidate(const Layer& L, const mnn_conv_options& o, mnn_scheme* cand, const Scratch& sc, hipStream_t s)
+{
+    Impl impl;
+    int rc = impl.prepare(L, *cand, o);
+    if (rc) return rc;
+    if ((rc = impl.run_stage(MNN_STAGE_FILTER, sc.x, sc.w, nullptr, sc.y, s))) return rc;
+    auto pass = [&]() -> int {
+        for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st) {
+            int r = impl.run_stage(st, sc.x, sc.w, nullptr, sc.y, s);
+            if (r) return r;
+        }
+        return MNN_OK;
+    };
+    for (int i = 0; i < o.plan_warmup; ++i)
+        if ((rc = pass())) return rc;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e;
+    if ((e = hipEventCreate(&e0)) != hipSuccess) return fail_hip(e, "hipEventCreate");
+    if ((e = hipEventCreate(&e1)) != hipSuccess) { (void)hipEventDestroy(e0); return fail_hip(e, "hipEventCreate"); }
+    float ms = -1.f;
+    rc = MNN_OK;
+    do {
+        if ((e = hipEventRecord(e0, s)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
+        for (int i = 0; i < o.plan_iters && !rc; ++i) rc = pass();
+        if (rc) break;
+        if ((e = hipEventRecord(e1, s)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
+        if ((e = hipEventSynchronize(e1)) != hipSuccess) { rc = fail_hip(e, "hipEventSynchronize"); break; }
+        if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) { rc = fail_hip(e, "hipEventElapsedTime"); break; }
+    } while (false);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    cand->est_ms = ms / (float)o.plan_iters;
+    return MNN_OK;
+}
+
+int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_conv_options* options, void* stream,
+              mnn_conv_plan_t* out_plan)
+{
+    if (!out_plan) return fail(MNN_E_INVALID_ARG, "out_plan must not be NULL");
+    Layer L;
+    int rc = validate(shape, geom, &L);
+    if (rc) return rc;
+    mnn_conv_options o;
+    if ((rc = validate_options(options, &o))) return rc;
+
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        return fail(MNN_E_NO_DEVICE, "no HIP device available (%s)", e == hipSuccess ? "count is 0" : hipGetErrorString(e));
+    }
+    int dev = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return fail_hip(e, "hipGetDevice");
+    hipStream_t s = (hipStream_t)stream;
+
+    mnn_conv_plan_s* plan = new (std::nothrow) mnn_conv_plan_s();
+    if (!plan) return fail(MNN_E_OOM, "host allocation failed");
+    plan->L = L;
+    plan->opt = o;
+    plan->device = dev;
+
+    mnn_scheme chosen;
+    if (o.force_kind != MNN_SCHEME_AUTO) {
+        int n = 0;
+        if (o.force_kind == MNN_SCHEME_WINOGRAD) {
+            n = o.force_tile_n;
+            if (n <= 0) {
+                n = analytic_tile(L.s.kh, L.s.c_in, L.s.c_out, L.Ho, L.Wo, o.alpha_max);
+                if (n < 2) n = 2;
+            }
+        }
+        chosen = make_scheme(o.force_kind, n, o.force_prec);
+        plan->cands.push_back(chosen);
+    } else {
+        plan->cands = enumerate(L, o);
+        bool hit = false;
+        const CacheKey key = cache_key(dev, L, o);
+        if (o.use_cache) {
+            std::lock_guard<std::mutex> lk(g_cache_mu);
+            auto it = g_cache.find(key);
+            if (it != g_cache.end()) { chosen = it->second; hit = true; }
+        }
+        if (!hit) {
+            if (plan->cands.size() == 1) {
+                chosen = plan->cands[0];
+            } else {
+                // scratch tensors for the timing launches (contents do not affect kernel time)
+                Scratch sc;
+                const size_t xb = (size_t)L.s.n * L.s.c_in * L.s.h * L.s.w * sizeof(float);
+                const size_t wb = (size_t)L.s.c_out * L.s.c_in * L.s.kh * L.s.kw * sizeof(float);
+                const size_t yb = (size_t)L.s.n * L.s.c_out * L.Ho * L.Wo * sizeof(float);
+                if ((e = hipMalloc((void**)&sc.x, xb)) != hipSuccess || (e = hipMalloc((void**)&sc.w, wb)) != hipSuccess ||
+                    (e = hipMalloc((void**)&sc.y, yb)) != hipSuccess) {
+                    delete plan;
+                    return fail_hip(e, "hipMalloc planner scratch");
+                }
+                if ((e = hipMemset(sc.x, 0, xb)) != hipSuccess || (e = hipMemset(sc.w, 0, wb)) != hipSuccess) {
+                    delete plan;
+                    return fail_hip(e, "hipMemset planner scratch");
+                }
+                for (auto& c : plan->cands) {
+                    rc = time_candidate(L, o, &c, sc, s);
+                    if (rc == MNN_E_OOM) { c.est_ms = -1.f; (void)hipGetLastError(); continue; }   // does not fit: not a candidate
+                    if (rc) { delete plan; return rc; }
+                }
+                const int pick = select_scheme(plan->cands.data(), (int)plan->cands.size(), L.s.kh);
+                if (pick < 0) { delete plan; return fail(MNN_E_OOM, "no candidate scheme could be timed"); }
+                chosen = plan->cands[pick];
+            }
+            if (o.use_cache) {
+                std::lock_guard<std::mutex> lk(g_cache_mu);
+                g_cache[key] = chosen;
+            }
+        } else {
+            plan->from_cache = true;
+        }
+    }
+    rc = plan->impl.prepare(L, chosen, o);
+    if (rc) { delete plan; return rc; }
+    *out_plan = plan;
+    return MNN_OK;
+}
+
+int check_run_args(mnn_conv_plan_t plan, const float* input, const float* weight, float* output)
+{
+    if (!plan) return fail(MNN_E_INVALID_ARG, "plan is NULL");
+    if (!input || !weight || !output) return fail(MNN_E_INVALID_ARG, "input, weight and output must not be NULL");
+    return MNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mnn_conv_options_default(mnn_conv_options* opt)
+{
+    if (!opt) return fail(MNN_E_INVALID_ARG, "opt is NULL");
+    default_options(opt);
+    return MNN_OK;
+}
+
+int mnn_conv_plan(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_conv_options* options,
+                  void* stream, mnn_conv_plan_t* out_plan)
+{
+    try {
+        return plan_impl(shape, geom, options, stream, out_plan);
+    } catch (const std::bad_alloc&) {
+        return fail(MNN_E_OOM, "host allocation failed");
+    } catch (...) {
+        return fail(MNN_E_INVALID_ARG, "unexpected exception in mnn_conv_plan");
+    }
+}
+
+int mnn_conv_plan_scheme(mnn_conv_plan_t plan, mnn_scheme* out)
+{
+    if (!plan || !out) return fail(MNN_E_INVALID_ARG, "NULL argument");
+    *out = plan->impl.scheme;
+    return MNN_OK;
+}
+
+int mnn_conv_plan_candidates(mnn_conv_plan_t plan, mnn_scheme* out, int32_t cap, int32_t* count)
+{
+    if (!plan || !count || cap < 0 || (cap > 0 && !out)) return fail(MNN_E_INVALID_ARG, "bad argument");
+    *count = (int32_t)plan->cands.size();
+    for (int i = 0; i < cap && i < (int)plan->cands.size(); ++i) out[i] = plan->cands[i];
+    return MNN_OK;
+}
+
+int mnn_conv_plan_info(mnn_conv_plan_t plan, mnn_plan_info* out)
+{
+    if (!plan || !out) return fail(MNN_E_INVALID_ARG, "NULL argument");
+    std::memset(out, 0, sizeof *out);
+    const Impl& im = plan->impl;
+    if (im.scheme.kind == MNN_SCHEME_WINOGRAD) {
+        out->alpha = im.wg.alpha; out->tile_n = im.wg.n; out->tiles_h = im.wg.th; out->tiles_w = im.wg.tw;
+        out->p = im.wg.P; out->ldp = im.wg.ldp;
+    }
+    out->ldk = im.ldk;
+    out->h_out = plan->L.Ho; out->w_out = plan->L.Wo;
+    return MNN_OK;
+}
+
+size_t mnn_conv_workspace_bytes(mnn_conv_plan_t plan) { return plan ? plan->impl.bytes() : 0; }
+
+int mnn_conv_run(mnn_conv_plan_t plan, const float* input, const float* weight, const float* bias, float* output,
+                 void* stream)
+{
+    int rc = check_run_args(plan, input, weight, output);
+    if (rc) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    Impl& im = plan->impl;
+    if (!plan->weights_valid || plan->cached_weight != weight) {
+        if ((rc = im.run_stage(MNN_STAGE_FILTER, input, weight, bias, output, s))) return rc;
+        plan->cached_weight = weight;
+        plan->weights_valid = true;
+    }
+    for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st)
+        if ((rc = im.run_stage(st, input, weight, bias, output, s))) return rc;
+    return MNN_OK;
+}
+
+int mnn_conv_run_stage(mnn_conv_plan_t plan, int32_t stage, const float* input, const float* weight,
+                       const float* bias, float* output, void* stream)
+{
+    int rc = check_run_args(plan, input, weight, output);
+    if (rc) return rc;
+    if (stage < 0 || stage >= MNN_STAGE_COUNT) return fail(MNN_E_INVALID_ARG, "unknown stage %d", stage);
+    rc = plan->impl.run_stage(stage, input, weight, bias, output, (hipStream_t)stream);
+    if (!rc && stage == MNN_STAGE_FILTER) { plan->cached_weight = weight; plan->weights_valid = true; }
+    return rc;
+}
+
+int mnn_conv_run_timed(mnn_conv_plan_t plan, const float* input, const float* weight, const float* bias,
+                       float* output, void* stream, int32_t iters, float* stage_ms)
+{
+    int rc = check_run_args(plan, input, weight, output);
+    if (rc) return rc;
+    if (iters <= 0 || !stage_ms) return fail(MNN_E_INVALID_ARG, "iters must be positive and stage_ms not NULL");
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t ev[MNN_STAGE_COUNT + 1] = {};
+    hipError_t e = hipSuccess;
+    for (auto& v : ev)
+        if ((e = hipEventCreate(&v)) != hipSuccess) break;
+    double acc[MNN_STAGE_COUNT] = {};
+    if (e == hipSuccess) {
+        for (int it = 0; it < iters && !rc; ++it) {
+            for (int st = 0; st < MNN_STAGE_COUNT && !rc; ++st) {
+                if ((e = hipEventRecord(ev[st], s)) != hipSuccess) break;
+                rc = plan->impl.run_stage(st, input, weight, bias, output, s);
+            }
+            if (rc || e != hipSuccess) break;
+            if ((e = hipEventRecord(ev[MNN_STAGE_COUNT], s)) != hipSuccess) break;
+            if ((e = hipEventSynchronize(ev[MNN_STAGE_COUNT])) != hipSuccess) break;
+            for (int st = 0; st < MNN_STAGE_COUNT; ++st) {
+                float ms = 0.f;
+                if ((e = hipEventElapsedTime(&ms, ev[st], ev[st + 1])) != hipSuccess) break;
+                if (plan->impl.has_stage(st)) acc[st] += ms;
+            }
+            if (e != hipSuccess) break;
+        }
+    }
+    for (auto& v : ev)
+        if (v) (void)hipEventDestroy(v);
+    if (rc) return rc;
+    if (e != hipSuccess) return fail_hip(e, "event timing");
+    plan->cached_weight = weight;
+    plan->weights_valid = true;
+    for (int st = 0; st < MNN_STAGE_COUNT; ++st) stage_ms[st] = (float)(acc[st] / iters);
+    return MNN_OK;
+}
+
+int mnn_conv_invalidate_weights(mnn_conv_plan_t plan)
+{
+    if (!plan) return fail(MNN_E_INVALID_ARG, "plan is NULL");
+    plan->weights_valid = false;
+    plan->cached_weight = nullptr;
+    return MNN_OK;
+}
+
+int mnn_conv_plan_buffer(mnn_conv_plan_t plan, int32_t which, void** ptr, size_t* bytes)
+{
+    if (!plan || !ptr || !bytes) return fail(MNN_E_INVALID_ARG, "NULL argument");
+    const Impl& im = plan->impl;
+    switch (which) {
+        case MNN_BUF_U: *ptr = im.U; *bytes = im.U_bytes; break;
+        case MNN_BUF_V: *ptr = im.V; *bytes = im.V_bytes; break;
+        case MNN_BUF_M: *ptr = im.M; *bytes = im.M_bytes; break;
+        default: return fail(MNN_E_INVALID_ARG, "unknown buffer %d", which);
+    }
+    return MNN_OK;
+}
+
+void mnn_conv_plan_destroy(mnn_conv_plan_t plan) { delete plan; }
+
+int mnn_conv_get_transforms(int32_t n, int32_t k, float f, float* AT, float* G, float* BT)
+{
+    if (!AT || !G || !BT) return fail(MNN_E_INVALID_ARG, "NULL output");
+    if (n < 1 || k < 1 || !(f > 0.f)) return fail(MNN_E_INVALID_ARG, "n, k and f must be positive");
+    WinogradMatrices m;
+    try {
+        if (!generate_winograd(n, k, (double)f, &m))
+            return fail(MNN_E_UNSUPPORTED, "F(%d,%d): alpha = %d is outside 2..%d", n, k, n + k - 1, kMaxAlpha);
+    } catch (...) {
+        return fail(MNN_E_OOM, "host allocation failed");
+    }
+    std::memcpy(AT, m.AT.data(), m.AT.size() * sizeof(float));
+    std::memcpy(G, m.G.data(), m.G.size() * sizeof(float));
+    std::memcpy(BT, m.BT.data(), m.BT.size() * sizeof(float));
+    return MNN_OK;
+}
+
+int mnn_conv_analytic_cost(int32_t k, int32_t i_c, int32_t o_c, int32_t o_h, int32_t o_w, int32_t n, double* cost)
+{
+    if (!cost || k < 1 || i_c < 1 || o_c < 1 || o_h < 1 || o_w < 1 || n < 1) return fail(MNN_E_INVALID_ARG, "bad argument");
+    *cost = analytic_cost(k, i_c, o_c, o_h, o_w, n);
+    return MNN_OK;
+}
+
+int mnn_conv_analytic_tile(int32_t k, int32_t i_c, int32_t o_c, int32_t o_h, int32_t o_w, int32_t alpha_max,
+                           int32_t* n_hat)
+{
+    if (!n_hat || k < 1 || i_c < 1 || o_c < 1 || o_h < 1 || o_w < 1 || alpha_max < k)
+        return fail(MNN_E_INVALID_ARG, "bad argument");
+    *n_hat = analytic_tile(k, i_c, o_c, o_h, o_w, alpha_max);
+    return MNN_OK;
+}
+
+int mnn_conv_enumerate(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_conv_options* options,
+                       mnn_scheme* out, int32_t cap, int32_t* count)
+{
+    if (!count || cap < 0 || (cap > 0 && !out)) return fail(MNN_E_INVALID_ARG, "bad argument");
+    Layer L;
+    int rc = validate(shape, geom, &L);
+    if (rc) return rc;
+    mnn_conv_options o;
+    if ((rc = validate_options(options, &o))) return rc;
+    try {
+        std::vector<mnn_scheme> c = enumerate(L, o);
+        *count = (int32_t)c.size();
+        for (int i = 0; i < cap && i < (int)c.size(); ++i) out[i] = c[i];
+    } catch (...) {
+        return fail(MNN_E_OOM, "host allocation failed");
+    }
+    return MNN_OK;
+}
+
+int mnn_conv_select(const mnn_scheme* cands, int32_t count, int32_t k, int32_t* chosen)
+{
+    if (!cands || count <= 0 || !chosen) return fail(MNN_E_INVALID_ARG, "bad argument");
+    const int pick = select_scheme(cands, count, k);
+    if (pick < 0) return fail(MNN_E_INVALID_ARG, "no candidate carries a time");
+    *chosen = pick;
+    return MNN_OK;
+}
+
+int mnn_conv_cache_size(void)
+{
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    return (int)g_cache.size();
+}
+
+void mnn_conv_cache_clear(void)
+{
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    g_cache.clear();
+}
+
+const char* mnn_last_error(void) { return g_err.c_str(); }
+
+int mnn_version(void) { return 100; }
+
+}  // extern "C"

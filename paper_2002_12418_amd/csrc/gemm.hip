@@ -1,0 +1,226 @@
+// Batched fp32 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32).
+//
+// This is the "basic matrix multiplication" unit everything compute-intensive
+// is lowered to (Sections 3.3.1 (2) and 3.5 of the MNN paper): the alpha^2
+// Winograd-domain products M_xi = U_xi V_xi and the 1x1 convolution
+// y_n = w x_n + b.
+//
+//   D_b[m][col] = sum_r At_b[r][m] * B_b[r][col] (+ bias[m])
+//
+// Both operands are stored with the reduction index r as the slow dimension, so
+// a [BK][BM] / [BK][BN] tile is a plain coalesced copy from global memory into
+// LDS, and an MFMA operand (lane l holds element [r = l/32][m = l%32]) is one
+// conflict-free ds_read_b32 per 32x32 tile.
+//
+// Workgroup: WM x WN wavefronts of 64 lanes; each wavefront owns a
+// (BM/WM) x (BN/WN) block made of 32x32 MFMA tiles held in accumulator VGPRs.
+// The K loop is double buffered through LDS with a register prefetch of the
+// next chunk; one barrier per chunk.
+//
+// Grid: one-dimensional, remapped so that the workgroups one XCD receives
+// (hardware deals consecutive workgroup ids round-robin to the 8 XCDs) are a
+// contiguous range of tiles: tiles that share a B column panel and an A batch
+// then hit the same L2.
+#include <hip/hip_runtime.h>
+#include "kernels.hpp"
+
+namespace mnnconv {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kXcds = 8;
+
+__device__ __forceinline__ int xcd_remap(int bid, int total)
+{
+    const int per = total / kXcds, rem = total % kXcds;
+    const int xcd = bid % kXcds, loc = bid / kXcds;
+    return xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool VEC>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, int tilesM, int tilesN, int total)
+{
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM / 32;          // 32x32 tiles per wavefront along m
+    constexpr int TN = BN / WN / 32;          // ... along columns
+    constexpr int A4 = BK * BM / 4;           // float4 slots of the A tile
+    constexpr int B4 = BK * BN / 4;
+    constexpr int LA = A4 / NT;               // slots per thread
+    constexpr int LB = B4 / NT;
+    static_assert(A4 % NT == 0 && B4 % NT == 0, "tile must divide evenly over the workgroup");
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 2 == 0, "tile shape");
+
+    __shared__ __attribute__((aligned(16))) float As[2][BK][BM];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave % WM, wn = wave / WM;
+
+    const int logical = xcd_remap((int)blockIdx.x, total);
+    const int tm = logical % tilesM;
+    const int t2 = logical / tilesM;
+    const int tn = t2 % tilesN;
+    const int b = t2 / tilesN;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const float* __restrict__ Ab = p.At + (long long)b * p.strideA_batch;
+    const float* __restrict__ Bb = p.B + (long long)b * p.strideB_batch;
+
+    // ---- per-thread load slots (fixed over the K loop except for the row)
+    int a_row[LA], a_col[LA];
+    bool a_ok[LA];
+#pragma unroll
+    for (int j = 0; j < LA; ++j) {
+        const int s = tid + j * NT;
+        a_row[j] = s / (BM / 4);
+        a_col[j] = (s % (BM / 4)) * 4;
+        a_ok[j] = (m0 + a_col[j]) < p.lda;
+    }
+    int b_row[LB], b_col[LB];
+    long long b_off[LB][VEC ? 1 : 4];
+    bool b_ok[LB][VEC ? 1 : 4];
+#pragma unroll
+    for (int j = 0; j < LB; ++j) {
+        const int s = tid + j * NT;
+        b_row[j] = s / (BN / 4);
+        b_col[j] = (s % (BN / 4)) * 4;
+#pragma unroll
+        for (int e = 0; e < (VEC ? 1 : 4); ++e) {
+            const int col = n0 + b_col[j] + e;
+            b_ok[j][e] = col < p.Ncols;
+            const int img = col / p.L, rest = col % p.L;
+            b_off[j][e] = (long long)img * p.strideB_img + rest;
+        }
+    }
+
+    float4 ra[LA], rb[LB];
+    auto load_global = [&](int r0) {
+#pragma unroll
+        for (int j = 0; j < LA; ++j) {
+            const int r = r0 + a_row[j];
+            if (a_ok[j] && r < p.R)
+                ra[j] = *reinterpret_cast<const float4*>(Ab + (long long)r * p.lda + m0 + a_col[j]);
+            else
+                ra[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int j = 0; j < LB; ++j) {
+            const int r = r0 + b_row[j];
+            const bool rok = r < p.R;
+            const float* rowp = Bb + (long long)r * p.strideB_row;
+            if constexpr (VEC) {
+                if (rok && b_ok[j][0])
+                    rb[j] = *reinterpret_cast<const float4*>(rowp + b_off[j][0]);
+                else
+                    rb[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            } else {
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (rok && b_ok[j][e]) ? rowp[b_off[j][e]] : 0.f;
+                rb[j] = make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < LA; ++j) *reinterpret_cast<float4*>(&As[buf][a_row[j]][a_col[j]]) = ra[j];
+#pragma unroll
+        for (int j = 0; j < LB; ++j) *reinterpret_cast<float4*>(&Bs[buf][b_row[j]][b_col[j]]) = rb[j];
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nchunks = (p.R + BK - 1) / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+
+    const int lrow = lane >> 5;               // which of the 2 reduction rows of an MFMA step
+    const int lcol = lane & 31;
+    const int am = wm * (BM / WM) + lcol;
+    const int bn = wn * (BN / WN) + lcol;
+
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const int buf = ch & 1;
+        if (ch + 1 < nchunks) load_global((ch + 1) * BK);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float av[TM], bv[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) av[i] = As[buf][kk + lrow][am + i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][kk + lrow][bn + j * 32];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        if (ch + 1 < nchunks) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds column lcol of each tile, rows 8*(r/4) + 4*(lane/32) + r%4
+    float* __restrict__ Db = p.D + (long long)b * p.strideD_batch;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * (BN / WN) + j * 32 + lcol;
+        if (col >= p.Ncols) continue;
+        const long long coff = (long long)(col / p.L) * p.strideD_img + (col % p.L);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int mbase = m0 + wm * (BM / WM) + i * 32 + 4 * lrow;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = mbase + 8 * (r / 4) + (r % 4);
+                if (m < p.M) {
+                    float v = acc[i][j][r];
+                    if (p.bias) v += p.bias[m];
+                    Db[coff + (long long)m * p.strideD_row] = v;
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int BK, int WM, int WN>
+hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
+{
+    const int tilesM = (p.M + BM - 1) / BM;
+    const int tilesN = (p.Ncols + BN - 1) / BN;
+    const long long total = (long long)tilesM * tilesN * p.batch;
+    if (total <= 0 || total >= (1ll << 31)) return hipErrorInvalidValue;
+    if (vec)
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, true>), dim3((unsigned)total), dim3(WM * WN * 64),
+                           0, s, p, tilesM, tilesN, (int)total);
+    else
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, false>), dim3((unsigned)total), dim3(WM * WN * 64),
+                           0, s, p, tilesM, tilesN, (int)total);
+    return hipGetLastError();
+}
+
+inline bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+}  // namespace
+
+hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s)
+{
+    if (!p.At || !p.B || !p.D) return hipErrorInvalidValue;
+    if (p.M <= 0 || p.Ncols <= 0 || p.R <= 0 || p.batch <= 0 || p.L <= 0) return hipErrorInvalidValue;
+    if (p.lda < p.M || (p.lda & 3) || !aligned16(p.At) || (p.strideA_batch & 3)) return hipErrorInvalidValue;
+    const bool vec = aligned16(p.B) && (p.L % 4 == 0) && (p.Ncols % 4 == 0) && (p.strideB_batch % 4 == 0) &&
+                     (p.strideB_img % 4 == 0) && (p.strideB_row % 4 == 0);
+    if (p.M <= 64) return launch_cfg<64, 128, 16, 1, 4>(p, vec, s);
+    return launch_cfg<128, 128, 16, 2, 2>(p, vec, s);
+}
+
+}  // namespace mnnconv

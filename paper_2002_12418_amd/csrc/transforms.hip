@@ -1,0 +1,245 @@
+// Winograd transform kernels for gfx950 (Section 3.3.1 of the MNN paper:
+// Y = A^T [ sum_channel (G W G^T) (.) (B^T X B) ] A).
+//
+// All three are bandwidth bound (a few FLOP per byte moved), so the layout is
+// chosen for coalescing: one lane owns one (channel, tile) pair, consecutive
+// lanes own consecutive tiles, and every store / load of the Winograd-domain
+// tensors V[xi][c][p] and M[xi][k][p] is contiguous across the wavefront.
+// The transform matrices arrive as kernel arguments, so they sit in SGPRs and
+// every multiply is a v_fma with a scalar operand.
+#include <hip/hip_runtime.h>
+#include "kernels.hpp"
+
+namespace mnnconv {
+
+namespace {
+
+constexpr int kMaxK = 7;   // largest kernel size with a Winograd path
+
+// ---------------------------------------------------------------- filter: U = G w G^T
+struct FilterMat { float g[kMaxAlphaT][kMaxK]; };
+
+__global__ __launch_bounds__(256) void filter_transform_kernel(WinoGeom g, FilterMat gm,
+                                                               const float* __restrict__ w,
+                                                               float* __restrict__ U)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)g.K * g.C) return;
+    const int kk = (int)(idx % g.K);
+    const int c = (int)(idx / g.K);
+    const int k = g.k, a = g.alpha;
+    const float* wp = w + ((long long)kk * g.C + c) * k * k;
+    float wl[kMaxK][kMaxK];
+    for (int r = 0; r < k; ++r)
+        for (int s = 0; s < k; ++s) wl[r][s] = wp[r * k + s];
+    // tmp = G w  (alpha x k)
+    float tmp[kMaxAlphaT][kMaxK];
+    for (int i = 0; i < a; ++i)
+        for (int s = 0; s < k; ++s) {
+            float acc = 0.f;
+            for (int r = 0; r < k; ++r) acc = fmaf(gm.g[i][r], wl[r][s], acc);
+            tmp[i][s] = acc;
+        }
+    // U = tmp G^T  (alpha x alpha)
+    for (int i = 0; i < a; ++i)
+        for (int j = 0; j < a; ++j) {
+            float acc = 0.f;
+            for (int s = 0; s < k; ++s) acc = fmaf(tmp[i][s], gm.g[j][s], acc);
+            U[((long long)(i * a + j) * g.C + c) * g.ldk + kk] = acc;
+        }
+}
+
+// ---------------------------------------------------------------- input: V = B^T d B
+template <int A>
+__global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg<A, A> bt,
+                                                              const float* __restrict__ x,
+                                                              float* __restrict__ V)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)g.C * g.P) return;
+    const int c = (int)(idx / g.P);
+    const int p = (int)(idx % g.P);
+    const int tx = p % g.tw;
+    const int t2 = p / g.tw;
+    const int ty = t2 % g.th;
+    const int img = t2 / g.th;
+    const int y0 = ty * g.n - g.pad_h;
+    const int x0 = tx * g.n - g.pad_w;
+    const float* xp = x + ((long long)img * g.C + c) * g.H * g.W;
+
+    float d[A][A];
+#pragma unroll
+    for (int i = 0; i < A; ++i) {
+        const int iy = y0 + i;
+        const bool rowok = (iy >= 0) && (iy < g.H);
+#pragma unroll
+        for (int j = 0; j < A; ++j) {
+            const int ix = x0 + j;
+            const bool ok = rowok && (ix >= 0) && (ix < g.W);
+            d[i][j] = ok ? xp[(long long)iy * g.W + ix] : 0.f;
+        }
+    }
+    // t = B^T d
+    float t[A][A];
+#pragma unroll
+    for (int i = 0; i < A; ++i)
+#pragma unroll
+        for (int j = 0; j < A; ++j) {
+            float acc = 0.f;
+#pragma unroll
+            for (int a = 0; a < A; ++a) acc = fmaf(bt.v[i][a], d[a][j], acc);
+            t[i][j] = acc;
+        }
+    // v = t B,  v[i][j] = sum_b t[i][b] B^T[j][b]
+    const long long plane = (long long)g.C * g.ldp;
+    float* vp = V + (long long)c * g.ldp + p;
+#pragma unroll
+    for (int i = 0; i < A; ++i)
+#pragma unroll
+        for (int j = 0; j < A; ++j) {
+            float acc = 0.f;
+#pragma unroll
+            for (int b = 0; b < A; ++b) acc = fmaf(t[i][b], bt.v[j][b], acc);
+            vp[(long long)(i * A + j) * plane] = acc;
+        }
+}
+
+// ---------------------------------------------------------------- output: y = A^T m A + bias
+template <int NT, int A>
+__global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatArg<NT, A> at,
+                                                               const float* __restrict__ M,
+                                                               const float* __restrict__ bias,
+                                                               float* __restrict__ y)
+{
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long long)g.K * g.P) return;
+    const int kk = (int)(idx / g.P);
+    const int p = (int)(idx % g.P);
+    const int tx = p % g.tw;
+    const int t2 = p / g.tw;
+    const int ty = t2 % g.th;
+    const int img = t2 / g.th;
+
+    const long long plane = (long long)g.K * g.ldp;
+    const float* mp = M + (long long)kk * g.ldp + p;
+    // t = A^T m   (NT x A), accumulated row of m by row of m
+    float t[NT][A];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int b = 0; b < A; ++b) t[i][b] = 0.f;
+#pragma unroll
+    for (int a = 0; a < A; ++a) {
+        float mrow[A];
+#pragma unroll
+        for (int b = 0; b < A; ++b) mrow[b] = mp[(long long)(a * A + b) * plane];
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int b = 0; b < A; ++b) t[i][b] = fmaf(at.v[i][a], mrow[b], t[i][b]);
+    }
+    const float bv = bias ? bias[kk] : 0.f;
+    float* yp = y + ((long long)img * g.K + kk) * g.Ho * g.Wo;
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const int oy = ty * NT + i;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int ox = tx * NT + j;
+            float acc = bv;
+#pragma unroll
+            for (int b = 0; b < A; ++b) acc = fmaf(t[i][b], at.v[j][b], acc);
+            if (oy < g.Ho && ox < g.Wo) yp[(long long)oy * g.Wo + ox] = acc;
+        }
+    }
+}
+
+template <int A>
+hipError_t launch_input_t(const WinoGeom& g, const float* BT, const float* x, float* V, hipStream_t s)
+{
+    MatArg<A, A> m;
+    for (int i = 0; i < A; ++i)
+        for (int j = 0; j < A; ++j) m.v[i][j] = BT[i * A + j];
+    const long long total = (long long)g.C * g.P;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(input_transform_kernel<A>, dim3(blocks), dim3(256), 0, s, g, m, x, V);
+    return hipGetLastError();
+}
+
+template <int NT, int A>
+hipError_t launch_output_t(const WinoGeom& g, const float* AT, const float* M, const float* bias,
+                           float* y, hipStream_t s)
+{
+    MatArg<NT, A> m;
+    for (int i = 0; i < NT; ++i)
+        for (int j = 0; j < A; ++j) m.v[i][j] = AT[i * A + j];
+    const long long total = (long long)g.K * g.P;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL((output_transform_kernel<NT, A>), dim3(blocks), dim3(256), 0, s, g, m, M, bias, y);
+    return hipGetLastError();
+}
+
+bool geom_ok(const WinoGeom& g)
+{
+    if (g.N <= 0 || g.C <= 0 || g.H <= 0 || g.W <= 0 || g.K <= 0) return false;
+    if (g.n < 2 || g.k < 2 || g.k > kMaxK || g.alpha != g.n + g.k - 1 || g.alpha > kMaxAlphaT) return false;
+    if (g.Ho != g.H + 2 * g.pad_h - g.k + 1 || g.Wo != g.W + 2 * g.pad_w - g.k + 1) return false;
+    if (g.Ho <= 0 || g.Wo <= 0) return false;
+    if (g.th != (g.Ho + g.n - 1) / g.n || g.tw != (g.Wo + g.n - 1) / g.n) return false;
+    if ((long long)g.P != (long long)g.N * g.th * g.tw) return false;
+    if (g.ldp < g.P || g.ldk < g.K) return false;
+    // every per-plane element count must fit the 32-bit tile arithmetic used in the kernels
+    if ((long long)g.C * g.ldp >= (1ll << 31) || (long long)g.K * g.ldp >= (1ll << 31)) return false;
+    if ((long long)g.H * g.W >= (1ll << 31)) return false;
+    return true;
+}
+
+}  // namespace
+
+bool winograd_kernels_available(int n, int k)
+{
+    const int a = n + k - 1;
+    return n >= 2 && n <= 8 && k >= 2 && k <= kMaxK && a <= kMaxAlphaT;
+}
+
+hipError_t launch_filter_transform(const WinoGeom& g, const float* G, const float* w, float* U, hipStream_t s)
+{
+    if (!geom_ok(g) || !G || !w || !U) return hipErrorInvalidValue;
+    FilterMat m;
+    for (int i = 0; i < kMaxAlphaT; ++i)
+        for (int j = 0; j < kMaxK; ++j) m.g[i][j] = (i < g.alpha && j < g.k) ? G[i * g.k + j] : 0.f;
+    const long long total = (long long)g.K * g.C;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(filter_transform_kernel, dim3(blocks), dim3(256), 0, s, g, m, w, U);
+    return hipGetLastError();
+}
+
+hipError_t launch_input_transform(const WinoGeom& g, const float* BT, const float* x, float* V, hipStream_t s)
+{
+    if (!geom_ok(g) || !BT || !x || !V) return hipErrorInvalidValue;
+    switch (g.alpha) {
+#define MNN_CASE(A) case A: return launch_input_t<A>(g, BT, x, V, s);
+        MNN_CASE(3) MNN_CASE(4) MNN_CASE(5) MNN_CASE(6) MNN_CASE(7) MNN_CASE(8)
+        MNN_CASE(9) MNN_CASE(10) MNN_CASE(11) MNN_CASE(12)
+#undef MNN_CASE
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_output_transform(const WinoGeom& g, const float* AT, const float* M, const float* bias,
+                                   float* y, hipStream_t s)
+{
+    if (!geom_ok(g) || !AT || !M || !y) return hipErrorInvalidValue;
+    if (!winograd_kernels_available(g.n, g.k)) return hipErrorInvalidValue;
+#define MNN_NK(NN, KK) \
+    if (g.n == NN && g.k == KK) return launch_output_t<NN, NN + KK - 1>(g, AT, M, bias, y, s);
+#define MNN_N(NN) MNN_NK(NN, 2) MNN_NK(NN, 3) MNN_NK(NN, 4) MNN_NK(NN, 5)
+    MNN_N(2) MNN_N(3) MNN_N(4) MNN_N(5) MNN_N(6) MNN_N(7) MNN_N(8)
+    MNN_NK(2, 6) MNN_NK(3, 6) MNN_NK(4, 6) MNN_NK(5, 6) MNN_NK(6, 6) MNN_NK(7, 6)
+    MNN_NK(2, 7) MNN_NK(3, 7) MNN_NK(4, 7) MNN_NK(5, 7) MNN_NK(6, 7)
+#undef MNN_N
+#undef MNN_NK
+    return hipErrorInvalidValue;
+}
+
+}  // namespace mnnconv

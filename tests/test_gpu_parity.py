@@ -1,0 +1,86 @@
+"""GPU parity: the HIP path through the C ABI against the float64 oracle, element by element.
+
+Tolerances (max|y - ref| / max|ref| over the whole output tensor): 1e-4 for the fp32 direct, GEMM,
+F(2,3) and F(4,3) schemes, 1e-3 for larger Winograd tiles.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from conv_workloads import config_layers, draw, small_parity_layers
+
+pytestmark = pytest.mark.gpu
+
+
+def mnn():
+    import paper_2002_12418_amd as m
+    return m
+
+
+def tol_for(scheme, k):
+    m = mnn()
+    if scheme.kind == m.SCHEME_WINOGRAD and scheme.tile_n + k - 1 > 6:
+        return 1e-3
+    return 1e-4
+
+
+def forced_options(layer):
+    """Every scheme that is admissible for the layer, as (label, Options)."""
+    m = mnn()
+    out = []
+    for s in m.enumerate_schemes(layer.n, layer.c_in, layer.h, layer.w, layer.c_out, layer.kh, layer.kw,
+                                 stride=layer.stride, pad=layer.pad, dil=layer.dil):
+        out.append((s.label(layer.kh), m.Options(force_kind=s.kind, force_tile_n=s.tile_n, force_prec=s.prec)))
+    return out
+
+
+def run_and_compare(layer, options, with_bias=True):
+    m = mnn()
+    x, w, b = draw(layer, with_bias=with_bias)
+    ref = oracle.conv2d(x, w, b, stride=layer.stride, pad=layer.pad, dil=layer.dil)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    bd = torch.from_numpy(b).cuda() if b is not None else None
+    with m.ConvPlan.for_layer(layer, options=options) as plan:
+        y = torch.full(plan.out_shape, float("nan"), dtype=torch.float32, device="cuda")
+        plan.run(xd, wd, bd, y)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        scheme = plan.scheme
+    assert got.shape == ref.shape
+    assert np.isfinite(got).all(), "output holds NaN/inf or unwritten elements"
+    return oracle.error_ratio(got, ref), scheme
+
+
+@pytest.mark.parametrize("layer", small_parity_layers(), ids=lambda l: l.name)
+def test_small_layers_every_scheme(layer):
+    for label, opt in forced_options(layer):
+        print(f"[case] {layer.name} {label}", flush=True)
+        err, scheme = run_and_compare(layer, opt)
+        assert err <= tol_for(scheme, layer.kh), (layer.name, label, err)
+
+
+@pytest.mark.parametrize("layer", small_parity_layers()[:4], ids=lambda l: l.name)
+def test_small_layers_no_bias(layer):
+    for label, opt in forced_options(layer):
+        print(f"[case] nobias {layer.name} {label}", flush=True)
+        err, scheme = run_and_compare(layer, opt, with_bias=False)
+        assert err <= tol_for(scheme, layer.kh), (layer.name, label, err)
+
+
+@pytest.mark.parametrize("layer", config_layers(1) + config_layers(2), ids=lambda l: l.name)
+def test_config1_and_2_every_scheme(layer):
+    for label, opt in forced_options(layer):
+        print(f"[case] {layer.name} {label}", flush=True)
+        err, scheme = run_and_compare(layer, opt)
+        assert err <= tol_for(scheme, layer.kh), (layer.name, label, err)
+
+
+@pytest.mark.parametrize("layer", config_layers(1) + config_layers(2), ids=lambda l: l.name)
+def test_planner_choice_is_correct_and_listed(layer):
+    m = mnn()
+    m.cache_clear()
+    err, scheme = run_and_compare(layer, None)
+    assert err <= tol_for(scheme, layer.kh)
+    if layer.stride != 1:
+        assert scheme.kind == m.SCHEME_DIRECT
