@@ -65,13 +65,25 @@ typedef struct {
     int32_t kind;             /* mnn_scheme_kind                                          */
     int32_t tile_n;           /* n of F(n,k); 0 unless kind == MNN_SCHEME_WINOGRAD        */
     int32_t prec;             /* mnn_gemm_prec                                            */
+    int32_t variant;          /* kernel arrangement of the scheme, see MNN_WINO_*; 0 otherwise */
     float   est_ms;           /* time measured by the planner; < 0 when it was not timed  */
 } mnn_scheme;
+
+/* Kernel arrangements of a Winograd scheme (all compute the same F(n,k)). */
+enum {
+    MNN_WINO_UNFUSED = 0,     /* input transform, batched GEMM writing M, output transform        */
+    MNN_WINO_FUSED_OUT_32 = 1,/* input transform, GEMM with the output transform in its epilogue,
+                                 32 channels x 32 tiles per workgroup; M is never stored           */
+    MNN_WINO_FUSED_OUT_64 = 2,/* the same with 64 channels x 64 tiles per workgroup of 8 wavefronts
+                                 (where the registers of two wavefronts per SIMD allow it)         */
+    MNN_WINO_VARIANTS = 3
+};
 
 typedef struct {
     int32_t force_kind;       /* MNN_SCHEME_AUTO or the scheme to use without timing      */
     int32_t force_tile_n;     /* with force_kind == WINOGRAD: the n to use (0 = analytic) */
     int32_t force_prec;       /* mnn_gemm_prec used for forced schemes                    */
+    int32_t force_variant;    /* MNN_WINO_* used for a forced Winograd scheme; -1 = time the variants */
     int32_t allow_bf16;       /* 1: AUTO may also time bf16 candidates                    */
     int32_t alpha_max;        /* largest n + k - 1 the planner may generate (default 8, max 12) */
     float   point_scale_f;    /* f of the Winograd generator (default 0.5)                */
@@ -93,16 +105,20 @@ enum {
 
 /* Plan buffers that tests may look at (device memory owned by the plan). */
 enum {
-    MNN_BUF_U = 0,            /* prepared weights.  Winograd: [alpha^2][C][ldk] (ldk = c_out rounded up to 4),
-                                 element (xi, c, k) = (G w[k][c] G^T)[xi / alpha][xi % alpha]        */
-    MNN_BUF_V = 1,            /* transformed input tiles  [alpha^2][C][ldp]  (ldp = P rounded up to 4) */
-    MNN_BUF_M = 2             /* products                 [alpha^2][c_out][ldp]                      */
+    MNN_BUF_U = 0,            /* prepared weights.  Winograd, unfused: [alpha^2][C][ldk] (ldk = c_out rounded up to 4),
+                                 element (xi, c, k) = (G w[k][c] G^T)[xi / alpha][xi % alpha];
+                                 fused variants: [b][c/4][a][kg][c%4][k%16], xi = a*alpha + b (kg groups of 16
+                                 output channels, channel groups padded to whole 16-channel chunks) */
+    MNN_BUF_V = 1,            /* transformed input tiles, unfused: [alpha^2][C][ldp] (ldp = P rounded up to 4);
+                                 fused variants: [b][c/4][a][pg][c%4][p%16]                          */
+    MNN_BUF_M = 2             /* products [alpha^2][c_out][ldp] (unfused variant only)               */
 };
 
 typedef struct {
     int32_t alpha, tile_n, tiles_h, tiles_w;  /* Winograd geometry (0 for other schemes)  */
     int32_t p;                /* number of tiles N * tiles_h * tiles_w                    */
     int32_t ldp, ldk;         /* leading dimensions of V/M rows and of U rows             */
+    int32_t kg, pg;           /* fused variants: allocated 16-wide groups along c_out and along P */
     int32_t h_out, w_out;
 } mnn_plan_info;
 
@@ -199,6 +215,25 @@ int mnn_conv_enumerate(const mnn_conv_shape* shape, const mnn_conv_geom* geom,
  * the least est_ms; among times within 2 % of it, the smallest alpha, then the
  * fp32 variant.  Candidates with est_ms < 0 are ignored.  Host only. */
 int mnn_conv_select(const mnn_scheme* cands, int32_t count, int32_t k, int32_t* chosen);
+
+/*
+ * The matrix-multiplication unit on its own (Sections 3.3.1 (2), 3.3.2): for b < batch
+ *   D_b[m][col] = sum_{r<R} At_b[r][m] * B_b[r][col]  (+ bias[m] when bias != NULL),  m < M, col < ncols.
+ * All pointers are device memory, float32.  At is the left operand stored transposed,
+ * At_b = At + b*strideA_batch, row length lda (multiple of 4, >= M, 16-byte aligned base).
+ * B element (r, col) lives at  B + b*strideB_batch + (col / L)*strideB_img + r*strideB_row + col % L,
+ * D element (m, col) at        D + b*strideD_batch + (col / L)*strideD_img + m*strideD_row + col % L
+ * (L = run of columns that is contiguous in memory; strides in elements).
+ * variant 0 picks the tile configuration from the shape; 1..mnn_gemm_variant_count()-1 force one.
+ */
+typedef struct {
+    int32_t M, ncols, R, batch, lda, L, variant;
+    int64_t strideA_batch, strideB_batch, strideB_img, strideB_row, strideD_batch, strideD_img, strideD_row;
+} mnn_gemm_desc;
+int mnn_gemm_f32(const mnn_gemm_desc* desc, const float* At, const float* B, const float* bias, float* D,
+                 void* stream);
+int mnn_gemm_variant_count(void);
+const char* mnn_gemm_variant_name(int32_t variant);
 
 /* Process-wide cache of planner choices keyed by device, shape, geometry and options. */
 int mnn_conv_cache_size(void);

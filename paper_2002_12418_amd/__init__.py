@@ -1,12 +1,22 @@
 """MI355X-native convolution library (Winograd F(n,k) / 1x1 GEMM / direct + planner).
 
 Thin ctypes binding over libmnnconv.so; every step of the path runs in the HIP
-kernels behind the C ABI declared in include/mnn_conv.h.
+kernels behind the C ABI declared in include/mnn_conv.h.  The binding is loaded
+on first use so that ``paper_2002_12418_amd.build`` can be imported (and the
+library rebuilt) without loading a stale shared object.
 """
-from .binding import (  # noqa: F401
-    ConvPlan, MnnError, Scheme, Options, lib, library_path,
-    get_transforms, analytic_cost, analytic_tile, enumerate_schemes, select_scheme,
-    cache_size, cache_clear, version,
-    SCHEME_AUTO, SCHEME_DIRECT, SCHEME_WINOGRAD, SCHEME_GEMM1X1, GEMM_FP32, GEMM_BF16,
-    STAGE_FILTER, STAGE_INPUT, STAGE_GEMM, STAGE_OUTPUT, STAGE_COUNT, BUF_U, BUF_V, BUF_M,
-)
+import importlib
+
+_binding = None
+
+
+def __getattr__(name):
+    global _binding
+    if name.startswith("__"):
+        raise AttributeError(name)
+    if _binding is None:
+        _binding = importlib.import_module(".binding", __name__)
+    try:
+        return getattr(_binding, name)
+    except AttributeError:
+        raise AttributeError(f"module {__name__!r} has no attribute {name!r}") from None

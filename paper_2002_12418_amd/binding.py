@@ -21,6 +21,7 @@ SCHEME_AUTO, SCHEME_DIRECT, SCHEME_WINOGRAD, SCHEME_GEMM1X1 = 0, 1, 2, 3
 GEMM_FP32, GEMM_BF16 = 0, 1
 STAGE_FILTER, STAGE_INPUT, STAGE_GEMM, STAGE_OUTPUT, STAGE_COUNT = 0, 1, 2, 3, 4
 BUF_U, BUF_V, BUF_M = 0, 1, 2
+WINO_UNFUSED, WINO_FUSED_OUT_32, WINO_FUSED_OUT_64 = 0, 1, 2
 _KIND_NAMES = {SCHEME_AUTO: "auto", SCHEME_DIRECT: "direct", SCHEME_WINOGRAD: "winograd", SCHEME_GEMM1X1: "gemm1x1"}
 
 
@@ -39,17 +40,23 @@ class _Geom(ctypes.Structure):
 
 
 class _Scheme(ctypes.Structure):
-    _fields_ = [("kind", c_int32), ("tile_n", c_int32), ("prec", c_int32), ("est_ms", c_float)]
+    _fields_ = [("kind", c_int32), ("tile_n", c_int32), ("prec", c_int32), ("variant", c_int32), ("est_ms", c_float)]
 
 
 class _Options(ctypes.Structure):
     _fields_ = [("force_kind", c_int32), ("force_tile_n", c_int32), ("force_prec", c_int32),
-                ("allow_bf16", c_int32), ("alpha_max", c_int32), ("point_scale_f", c_float),
+                ("force_variant", c_int32), ("allow_bf16", c_int32), ("alpha_max", c_int32), ("point_scale_f", c_float),
                 ("plan_warmup", c_int32), ("plan_iters", c_int32), ("use_cache", c_int32)]
 
 
+class _GemmDesc(ctypes.Structure):
+    _fields_ = [(n, c_int32) for n in ("M", "ncols", "R", "batch", "lda", "L", "variant")] + \
+               [(n, ctypes.c_int64) for n in ("strideA_batch", "strideB_batch", "strideB_img", "strideB_row",
+                                              "strideD_batch", "strideD_img", "strideD_row")]
+
+
 class _Info(ctypes.Structure):
-    _fields_ = [(n, c_int32) for n in ("alpha", "tile_n", "tiles_h", "tiles_w", "p", "ldp", "ldk", "h_out", "w_out")]
+    _fields_ = [(n, c_int32) for n in ("alpha", "tile_n", "tiles_h", "tiles_w", "p", "ldp", "ldk", "kg", "pg", "h_out", "w_out")]
 
 
 def _load() -> ctypes.CDLL:
@@ -82,6 +89,10 @@ def _load() -> ctypes.CDLL:
     L.mnn_conv_enumerate.argtypes = [POINTER(_Shape), POINTER(_Geom), POINTER(_Options), POINTER(_Scheme), c_int32,
                                      POINTER(c_int32)]
     L.mnn_conv_select.argtypes = [POINTER(_Scheme), c_int32, c_int32, POINTER(c_int32)]
+    L.mnn_gemm_f32.argtypes = [POINTER(_GemmDesc), vp, vp, vp, vp, vp]
+    L.mnn_gemm_variant_count.argtypes = []
+    L.mnn_gemm_variant_name.argtypes = [c_int32]
+    L.mnn_gemm_variant_name.restype = c_char_p
     L.mnn_conv_cache_size.argtypes = []
     L.mnn_conv_cache_clear.argtypes = []
     L.mnn_conv_cache_clear.restype = None
@@ -111,20 +122,22 @@ class Scheme:
     kind: int
     tile_n: int = 0
     prec: int = GEMM_FP32
+    variant: int = 0
     est_ms: float = -1.0
 
     def label(self, k: Optional[int] = None) -> str:
         p = "" if self.prec == GEMM_FP32 else "/bf16"
         if self.kind == SCHEME_WINOGRAD:
-            return f"F({self.tile_n},{k if k is not None else 'k'}){p}"
+            v = {WINO_UNFUSED: "", WINO_FUSED_OUT_32: "+fo32", WINO_FUSED_OUT_64: "+fo64"}.get(self.variant, f"+v{self.variant}")
+            return f"F({self.tile_n},{k if k is not None else 'k'}){v}{p}"
         return _KIND_NAMES.get(self.kind, str(self.kind)) + p
 
     def _c(self) -> _Scheme:
-        return _Scheme(self.kind, self.tile_n, self.prec, self.est_ms)
+        return _Scheme(self.kind, self.tile_n, self.prec, self.variant, self.est_ms)
 
     @staticmethod
     def _from(c: _Scheme) -> "Scheme":
-        return Scheme(int(c.kind), int(c.tile_n), int(c.prec), float(c.est_ms))
+        return Scheme(int(c.kind), int(c.tile_n), int(c.prec), int(c.variant), float(c.est_ms))
 
 
 @dataclass
@@ -132,6 +145,7 @@ class Options:
     force_kind: int = SCHEME_AUTO
     force_tile_n: int = 0
     force_prec: int = GEMM_FP32
+    force_variant: int = -1
     allow_bf16: int = 0
     alpha_max: int = 8
     point_scale_f: float = 0.5
@@ -140,7 +154,7 @@ class Options:
     use_cache: int = 1
 
     def _c(self) -> _Options:
-        return _Options(self.force_kind, self.force_tile_n, self.force_prec, self.allow_bf16, self.alpha_max,
+        return _Options(self.force_kind, self.force_tile_n, self.force_prec, self.force_variant, self.allow_bf16, self.alpha_max,
                         self.point_scale_f, self.plan_warmup, self.plan_iters, self.use_cache)
 
     @staticmethod
@@ -199,6 +213,23 @@ def select_scheme(cands: Sequence[Scheme], k: int) -> int:
     out = c_int32()
     _check(lib.mnn_conv_select(arr, len(cands), k, byref(out)))
     return int(out.value)
+
+
+def gemm_variants() -> List[str]:
+    return [lib.mnn_gemm_variant_name(i).decode() for i in range(lib.mnn_gemm_variant_count())]
+
+
+def gemm_f32(At, B, D, bias=None, *, M, ncols, R, batch=1, lda=None, L=None, variant=0,
+             strideA_batch=0, strideB_batch=0, strideB_img=0, strideB_row=None,
+             strideD_batch=0, strideD_img=0, strideD_row=None, stream=None):
+    """mnn_gemm_f32 on device tensors (only their data_ptr() is used)."""
+    L = ncols if L is None else L
+    d = _GemmDesc(M, ncols, R, batch, M if lda is None else lda, L, variant, strideA_batch, strideB_batch,
+                  strideB_img, L if strideB_row is None else strideB_row, strideD_batch, strideD_img,
+                  L if strideD_row is None else strideD_row)
+    _check(lib.mnn_gemm_f32(byref(d), At.data_ptr(), B.data_ptr(), bias.data_ptr() if bias is not None else None,
+                            D.data_ptr(), _stream_handle(stream)))
+    return D
 
 
 def cache_size() -> int:

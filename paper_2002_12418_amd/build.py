@@ -16,7 +16,7 @@ INCLUDE = os.path.join(os.path.dirname(PKG), "include")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(PKG, "libmnnconv.so")
 
-SOURCES = ["api.cpp", "transforms.hip", "gemm.hip", "direct.hip"]
+SOURCES = ["api.cpp", "transforms.hip", "gemm.hip", "direct.hip", "wino_fused.hip", "gemm_async.hip"]
 
 # -packed-fp32-ops is switched off: hand-checked scalar fp32 code only.
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I", INCLUDE, "-I", CSRC,
@@ -46,7 +46,7 @@ def _compile(src: str) -> str:
 def build_library(verbose: bool = True) -> str:
     """Compile every source for gfx950 and link paper_2002_12418_amd/libmnnconv.so."""
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = LIB_PATH + ".tmp"
     cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs

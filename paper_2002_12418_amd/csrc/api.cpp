@@ -49,6 +49,7 @@ void default_options(mnn_conv_options* o)
     o->force_kind = MNN_SCHEME_AUTO;
     o->force_tile_n = 0;
     o->force_prec = MNN_GEMM_FP32;
+    o->force_variant = -1;
     o->allow_bf16 = 0;
     o->alpha_max = 8;
     o->point_scale_f = 0.5f;
@@ -98,6 +99,8 @@ int validate_options(const mnn_conv_options* in, mnn_conv_options* o)
         return fail(MNN_E_INVALID_ARG, "unknown force_kind %d", o->force_kind);
     if (o->force_prec != MNN_GEMM_FP32 && o->force_prec != MNN_GEMM_BF16)
         return fail(MNN_E_INVALID_ARG, "unknown force_prec %d", o->force_prec);
+    if (o->force_variant < -1 || o->force_variant >= MNN_WINO_VARIANTS)
+        return fail(MNN_E_INVALID_ARG, "unknown force_variant %d", o->force_variant);
     return MNN_OK;
 }
 
@@ -112,11 +115,28 @@ bool winograd_admissible(const Layer& L)
            L.g.dil_w == 1;
 }
 
-mnn_scheme make_scheme(int kind, int n, int prec)
+mnn_scheme make_scheme(int kind, int n, int prec, int variant = 0)
 {
     mnn_scheme s;
-    s.kind = kind; s.tile_n = n; s.prec = prec; s.est_ms = -1.f;
+    s.kind = kind; s.tile_n = n; s.prec = prec; s.variant = variant; s.est_ms = -1.f;
     return s;
+}
+
+bool wino_variant_available(int n, int k, int variant)
+{
+    if (!winograd_kernels_available(n, k)) return false;
+    switch (variant) {
+        case MNN_WINO_UNFUSED: return true;
+        case MNN_WINO_FUSED_OUT_32: return wino_fused_available(n, k);
+        case MNN_WINO_FUSED_OUT_64: return wino_fused_has_big_block(n, k);
+        default: return false;
+    }
+}
+
+void push_wino_variants(std::vector<mnn_scheme>* out, int n, int k, int prec)
+{
+    for (int v = 0; v < MNN_WINO_VARIANTS; ++v)
+        if (wino_variant_available(n, k, v)) out->push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, prec, v));
 }
 
 // Section 3.2 (1): k = 1 -> matrix multiplication; k > 1 -> sliding window or F(n,k).
@@ -130,8 +150,7 @@ std::vector<mnn_scheme> enumerate(const Layer& L, const mnn_conv_options& o)
     out.push_back(make_scheme(MNN_SCHEME_DIRECT, 0, MNN_GEMM_FP32));
     if (winograd_admissible(L)) {
         const int k = L.s.kh;
-        for (int n = 2; n + k - 1 <= o.alpha_max; ++n)
-            if (winograd_kernels_available(n, k)) out.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, MNN_GEMM_FP32));
+        for (int n = 2; n + k - 1 <= o.alpha_max; ++n) push_wino_variants(&out, n, k, MNN_GEMM_FP32);
     }
     return out;
 }
@@ -166,11 +185,68 @@ int select_scheme(const mnn_scheme* c, int count, int k)
     for (int i = 0; i < count; ++i) {
         if (c[i].est_ms < 0.f || c[i].est_ms > limit) continue;
         if (pick < 0) { pick = i; continue; }
-        const auto ki = std::make_tuple(alpha_of(c[i]), c[i].prec, c[i].est_ms);
-        const auto kp = std::make_tuple(alpha_of(c[pick]), c[pick].prec, c[pick].est_ms);
+        const auto ki = std::make_tuple(alpha_of(c[i]), c[i].prec, c[i].est_ms, c[i].variant);
+        const auto kp = std::make_tuple(alpha_of(c[pick]), c[pick].prec, c[pick].est_ms, c[pick].variant);
         if (ki < kp) pick = i;
     }
     return pick;
+}
+
+// ------------------------------------------------------------------ GEMM tile configuration per shape
+// The matrix-multiplication stage has several tile configurations; which one is fastest depends on
+// the shape (how many tiles there are to fill 256 CUs, how long the reduction is).  Like the scheme
+// itself it is chosen by measurement at pre-inference time and remembered per shape.
+using GemmKey = std::tuple<int, std::vector<long long>>;
+std::mutex g_gemm_mu;
+std::map<GemmKey, int> g_gemm_choice;
+
+GemmKey gemm_key(int device, const GemmProblem& p)
+{
+    std::vector<long long> v = {p.M, p.Ncols, p.R, p.batch, p.lda, p.L, p.strideA_batch, p.strideB_batch, p.strideB_img,
+                                p.strideB_row, p.strideD_batch, p.strideD_img, p.strideD_row, p.bias ? 1 : 0};
+    return GemmKey(device, v);
+}
+
+// Times every usable configuration on the given (valid, writable) buffers; returns the fastest id.
+int tune_gemm(GemmProblem p, hipStream_t s, int* variant_out)
+{
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const GemmKey key = gemm_key(dev, p);
+    {
+        std::lock_guard<std::mutex> lk(g_gemm_mu);
+        auto it = g_gemm_choice.find(key);
+        if (it != g_gemm_choice.end()) { *variant_out = it->second; return MNN_OK; }
+    }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e;
+    if ((e = hipEventCreate(&e0)) != hipSuccess) return fail_hip(e, "hipEventCreate");
+    if ((e = hipEventCreate(&e1)) != hipSuccess) { (void)hipEventDestroy(e0); return fail_hip(e, "hipEventCreate"); }
+    int best = 0;
+    float best_ms = -1.f;
+    const int iters = 4;
+    int rc = MNN_OK;
+    for (int v = 1; v < gemm_f32_variant_count() && !rc; ++v) {
+        p.variant = v;
+        e = launch_gemm_f32(p, s);                                   // warm-up, also tells whether v applies
+        if (e == hipErrorInvalidValue) { (void)hipGetLastError(); continue; }
+        if (e != hipSuccess) { rc = fail_hip(e, "gemm tuning launch"); break; }
+        if ((e = hipEventRecord(e0, s)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
+        for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_gemm_f32(p, s);
+        if (e != hipSuccess) { rc = fail_hip(e, "gemm tuning launch"); break; }
+        if ((e = hipEventRecord(e1, s)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
+        if ((e = hipEventSynchronize(e1)) != hipSuccess) { rc = fail_hip(e, "hipEventSynchronize"); break; }
+        float ms = 0.f;
+        if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) { rc = fail_hip(e, "hipEventElapsedTime"); break; }
+        if (best_ms < 0.f || ms < best_ms) { best_ms = ms; best = v; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    *variant_out = best;
+    std::lock_guard<std::mutex> lk(g_gemm_mu);
+    g_gemm_choice[key] = best;
+    return MNN_OK;
 }
 
 // ------------------------------------------------------------------ one realised scheme
@@ -184,6 +260,7 @@ struct Impl {
     float* V = nullptr; size_t V_bytes = 0;
     float* M = nullptr; size_t M_bytes = 0;
     int ldk = 0;
+    int gemm_variant = 0;      // tile configuration of the GEMM stage (0 = shape heuristic)
 
     ~Impl() { release(); }
     Impl() = default;
@@ -233,12 +310,28 @@ struct Impl {
             if (P >= (1ll << 30)) return fail(MNN_E_UNSUPPORTED, "too many tiles");
             wg.P = (int)P; wg.ldp = round_up(wg.P, 4); wg.ldk = ldk;
             const size_t a2 = (size_t)wg.alpha * wg.alpha;
+            if (!wino_variant_available(n, k, s.variant))
+                return fail(MNN_E_UNSUPPORTED, "Winograd variant %d is not available for F(%d,%d)", s.variant, n, k);
+            int rc;
+            if (s.variant != MNN_WINO_UNFUSED) {
+                // blocked operands, padded so that whole 128-wide blocks can be copied unchecked
+                wg.blocked = 1;
+                wg.cchunks = round_up((sh.c_in + 3) / 4, 4);          // whole 16-channel chunks
+                wg.kg = round_up((sh.c_out + 15) / 16, 8);
+                wg.pg = round_up((wg.P + 15) / 16, 8);
+                U_bytes = (size_t)wg.cchunks * a2 * wg.kg * 64 * sizeof(float);
+                V_bytes = (size_t)wg.cchunks * a2 * wg.pg * 64 * sizeof(float);
+                if (V_bytes >= ((size_t)1 << 40) || U_bytes >= ((size_t)1 << 40))
+                    return fail(MNN_E_UNSUPPORTED, "Winograd-domain tensors too large");
+                if ((rc = alloc_zero(&U, U_bytes, "hipMalloc U"))) return rc;
+                if ((rc = alloc_zero(&V, V_bytes, "hipMalloc V"))) return rc;
+                return MNN_OK;
+            }
             if ((long long)wg.C * wg.ldp >= (1ll << 31) || (long long)wg.K * wg.ldp >= (1ll << 31))
                 return fail(MNN_E_UNSUPPORTED, "Winograd-domain plane too large");
             U_bytes = a2 * sh.c_in * ldk * sizeof(float);
             V_bytes = a2 * sh.c_in * wg.ldp * sizeof(float);
             M_bytes = a2 * sh.c_out * wg.ldp * sizeof(float);
-            int rc;
             if ((rc = alloc_zero(&U, U_bytes, "hipMalloc U"))) return rc;
             if ((rc = alloc_zero(&V, V_bytes, "hipMalloc V"))) return rc;
             if ((rc = alloc_zero(&M, M_bytes, "hipMalloc M"))) return rc;
@@ -260,10 +353,65 @@ struct Impl {
         return fail(MNN_E_INVALID_ARG, "unknown scheme kind %d", s.kind);
     }
 
+    GemmProblem wino_gemm_problem() const
+    {
+        GemmProblem p{};
+        p.At = U; p.B = V; p.D = M; p.bias = nullptr;
+        p.M = wg.K; p.Ncols = wg.ldp; p.R = wg.C; p.batch = wg.alpha * wg.alpha;
+        p.lda = ldk; p.L = wg.ldp;
+        p.strideA_batch = (long long)wg.C * ldk;
+        p.strideB_batch = (long long)wg.C * wg.ldp; p.strideB_img = 0; p.strideB_row = wg.ldp;
+        p.strideD_batch = (long long)wg.K * wg.ldp; p.strideD_img = 0; p.strideD_row = wg.ldp;
+        p.variant = gemm_variant;
+        return p;
+    }
+
+    GemmProblem pointwise_gemm_problem(const float* x, const float* b, float* y) const
+    {
+        const mnn_conv_shape& sh = L.s;
+        const int HW = sh.h * sh.w;
+        GemmProblem p{};
+        p.At = U; p.B = x; p.D = y; p.bias = b;
+        p.M = sh.c_out; p.Ncols = sh.n * HW; p.R = sh.c_in; p.batch = 1;
+        p.lda = ldk; p.L = HW;
+        p.strideA_batch = 0;
+        p.strideB_batch = 0; p.strideB_img = (long long)sh.c_in * HW; p.strideB_row = HW;
+        p.strideD_batch = 0; p.strideD_img = (long long)sh.c_out * HW; p.strideD_row = HW;
+        p.variant = gemm_variant;
+        return p;
+    }
+
+    // Picks the GEMM tile configuration by timing (pre-inference).  The 1x1 scheme multiplies the
+    // caller's tensors, so it is tuned on scratch tensors of the layer's size.
+    int tune(hipStream_t s)
+    {
+        if (scheme.kind == MNN_SCHEME_WINOGRAD && scheme.variant == MNN_WINO_UNFUSED)
+            return tune_gemm(wino_gemm_problem(), s, &gemm_variant);
+        if (scheme.kind == MNN_SCHEME_GEMM1X1) {
+            const mnn_conv_shape& sh = L.s;
+            const size_t xb = (size_t)sh.n * sh.c_in * sh.h * sh.w * sizeof(float);
+            const size_t yb = (size_t)sh.n * sh.c_out * sh.h * sh.w * sizeof(float);
+            float *tx = nullptr, *ty = nullptr, *tb = nullptr;
+            hipError_t e;
+            int rc = MNN_OK;
+            if ((e = hipMalloc((void**)&tx, xb)) != hipSuccess || (e = hipMalloc((void**)&ty, yb)) != hipSuccess ||
+                (e = hipMalloc((void**)&tb, (size_t)sh.c_out * sizeof(float))) != hipSuccess)
+                rc = fail_hip(e, "hipMalloc tuning scratch");
+            if (!rc && ((e = hipMemset(tx, 0, xb)) != hipSuccess || (e = hipMemset(tb, 0, (size_t)sh.c_out * sizeof(float))) != hipSuccess))
+                rc = fail_hip(e, "hipMemset tuning scratch");
+            if (!rc) rc = tune_gemm(pointwise_gemm_problem(tx, tb, ty), s, &gemm_variant);
+            if (tx) (void)hipFree(tx);
+            if (ty) (void)hipFree(ty);
+            if (tb) (void)hipFree(tb);
+            return rc;
+        }
+        return MNN_OK;
+    }
+
     bool has_stage(int st) const
     {
         switch (scheme.kind) {
-            case MNN_SCHEME_WINOGRAD: return true;
+            case MNN_SCHEME_WINOGRAD: return scheme.variant == MNN_WINO_UNFUSED || st != MNN_STAGE_OUTPUT;
             case MNN_SCHEME_GEMM1X1: return st == MNN_STAGE_FILTER || st == MNN_STAGE_GEMM;
             default: return st == MNN_STAGE_GEMM;
         }
@@ -279,14 +427,11 @@ struct Impl {
                 case MNN_STAGE_FILTER: e = launch_filter_transform(wg, mats.G.data(), w, U, s); break;
                 case MNN_STAGE_INPUT: e = launch_input_transform(wg, mats.BT.data(), x, V, s); break;
                 case MNN_STAGE_GEMM: {
-                    GemmProblem p{};
-                    p.At = U; p.B = V; p.D = M; p.bias = nullptr;
-                    p.M = wg.K; p.Ncols = wg.ldp; p.R = wg.C; p.batch = wg.alpha * wg.alpha;
-                    p.lda = ldk; p.L = wg.ldp;
-                    p.strideA_batch = (long long)wg.C * ldk;
-                    p.strideB_batch = (long long)wg.C * wg.ldp; p.strideB_img = 0; p.strideB_row = wg.ldp;
-                    p.strideD_batch = (long long)wg.K * wg.ldp; p.strideD_img = 0; p.strideD_row = wg.ldp;
-                    e = launch_gemm_f32(p, s);
+                    if (scheme.variant != MNN_WINO_UNFUSED) {
+                        e = launch_wino_fused(wg, scheme.variant - 1, mats.AT.data(), U, V, b, y, s);
+                        break;
+                    }
+                    e = launch_gemm_f32(wino_gemm_problem(), s);
                     break;
                 }
                 case MNN_STAGE_OUTPUT: e = launch_output_transform(wg, mats.AT.data(), M, b, y, s); break;
@@ -296,14 +441,7 @@ struct Impl {
             if (st == MNN_STAGE_FILTER) {
                 e = launch_weight_transpose(w, U, sh.c_out, sh.c_in, ldk, s);
             } else {
-                GemmProblem p{};
-                p.At = U; p.B = x; p.D = y; p.bias = b;
-                p.M = sh.c_out; p.Ncols = sh.n * HW; p.R = sh.c_in; p.batch = 1;
-                p.lda = ldk; p.L = HW;
-                p.strideA_batch = 0;
-                p.strideB_batch = 0; p.strideB_img = (long long)sh.c_in * HW; p.strideB_row = HW;
-                p.strideD_batch = 0; p.strideD_img = (long long)sh.c_out * HW; p.strideD_row = HW;
-                e = launch_gemm_f32(p, s);
+                e = launch_gemm_f32(pointwise_gemm_problem(x, b, y), s);
             }
         } else {
             e = launch_direct_conv(dg, x, w, b, y, s);
@@ -360,6 +498,7 @@ int time_candidate(const Layer& L, const mnn_conv_options& o, mnn_scheme* cand, 
     Impl impl;
     int rc = impl.prepare(L, *cand, o);
     if (rc) return rc;
+    if ((rc = impl.tune(s))) return rc;
     if ((rc = impl.run_stage(MNN_STAGE_FILTER, sc.x, sc.w, nullptr, sc.y, s))) return rc;
     auto pass = [&]() -> int {
         for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st) {
@@ -418,22 +557,30 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
     plan->device = dev;
 
     mnn_scheme chosen;
+    bool use_cache = o.use_cache != 0;
     if (o.force_kind != MNN_SCHEME_AUTO) {
-        int n = 0;
+        use_cache = false;
         if (o.force_kind == MNN_SCHEME_WINOGRAD) {
-            n = o.force_tile_n;
+            int n = o.force_tile_n;
             if (n <= 0) {
                 n = analytic_tile(L.s.kh, L.s.c_in, L.s.c_out, L.Ho, L.Wo, o.alpha_max);
                 if (n < 2) n = 2;
             }
+            if (o.force_variant >= 0)
+                plan->cands.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, o.force_prec, o.force_variant));
+            else if (winograd_admissible(L))
+                push_wino_variants(&plan->cands, n, L.s.kh, o.force_prec);   // time the arrangements of this F(n,k)
+            if (plan->cands.empty()) plan->cands.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, o.force_prec, 0));
+        } else {
+            plan->cands.push_back(make_scheme(o.force_kind, 0, o.force_prec));
         }
-        chosen = make_scheme(o.force_kind, n, o.force_prec);
-        plan->cands.push_back(chosen);
     } else {
         plan->cands = enumerate(L, o);
+    }
+    {
         bool hit = false;
         const CacheKey key = cache_key(dev, L, o);
-        if (o.use_cache) {
+        if (use_cache) {
             std::lock_guard<std::mutex> lk(g_cache_mu);
             auto it = g_cache.find(key);
             if (it != g_cache.end()) { chosen = it->second; hit = true; }
@@ -465,7 +612,7 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
                 if (pick < 0) { delete plan; return fail(MNN_E_OOM, "no candidate scheme could be timed"); }
                 chosen = plan->cands[pick];
             }
-            if (o.use_cache) {
+            if (use_cache) {
                 std::lock_guard<std::mutex> lk(g_cache_mu);
                 g_cache[key] = chosen;
             }
@@ -474,6 +621,7 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
         }
     }
     rc = plan->impl.prepare(L, chosen, o);
+    if (!rc) rc = plan->impl.tune(s);
     if (rc) { delete plan; return rc; }
     *out_plan = plan;
     return MNN_OK;
@@ -531,7 +679,7 @@ int mnn_conv_plan_info(mnn_conv_plan_t plan, mnn_plan_info* out)
     const Impl& im = plan->impl;
     if (im.scheme.kind == MNN_SCHEME_WINOGRAD) {
         out->alpha = im.wg.alpha; out->tile_n = im.wg.n; out->tiles_h = im.wg.th; out->tiles_w = im.wg.tw;
-        out->p = im.wg.P; out->ldp = im.wg.ldp;
+        out->p = im.wg.P; out->ldp = im.wg.ldp; out->kg = im.wg.kg; out->pg = im.wg.pg;
     }
     out->ldk = im.ldk;
     out->h_out = plan->L.Ho; out->w_out = plan->L.Wo;
@@ -690,6 +838,26 @@ int mnn_conv_select(const mnn_scheme* cands, int32_t count, int32_t k, int32_t* 
     *chosen = pick;
     return MNN_OK;
 }
+
+int mnn_gemm_f32(const mnn_gemm_desc* d, const float* At, const float* B, const float* bias, float* D, void* stream)
+{
+    if (!d || !At || !B || !D) return fail(MNN_E_INVALID_ARG, "NULL argument");
+    GemmProblem p{};
+    p.At = At; p.B = B; p.D = D; p.bias = bias;
+    p.M = d->M; p.Ncols = d->ncols; p.R = d->R; p.batch = d->batch; p.lda = d->lda; p.L = d->L;
+    p.variant = d->variant;
+    p.strideA_batch = d->strideA_batch;
+    p.strideB_batch = d->strideB_batch; p.strideB_img = d->strideB_img; p.strideB_row = d->strideB_row;
+    p.strideD_batch = d->strideD_batch; p.strideD_img = d->strideD_img; p.strideD_row = d->strideD_row;
+    hipError_t e = launch_gemm_f32(p, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) { (void)hipGetLastError(); return fail(MNN_E_INVALID_ARG, "GEMM descriptor rejected (sizes, lda, alignment or variant)"); }
+    if (e != hipSuccess) return fail_hip(e, "gemm launch");
+    return MNN_OK;
+}
+
+int mnn_gemm_variant_count(void) { return gemm_f32_variant_count(); }
+
+const char* mnn_gemm_variant_name(int32_t variant) { return gemm_f32_variant_name(variant); }
 
 int mnn_conv_cache_size(void)
 {

@@ -212,15 +212,46 @@ inline bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 
 
 }  // namespace
 
+namespace {
+struct Variant { const char* name; hipError_t (*fn)(const GemmProblem&, bool, hipStream_t); int bm, bn; };
+const Variant kVariants[] = {
+    {"auto", nullptr, 0, 0},
+    {"128x128x16_w2x2", launch_cfg<128, 128, 16, 2, 2>, 128, 128},
+    {"64x128x16_w1x4", launch_cfg<64, 128, 16, 1, 4>, 64, 128},
+    {"128x128x32_w2x2", launch_cfg<128, 128, 32, 2, 2>, 128, 128},
+    {"128x64x16_w2x2", launch_cfg<128, 64, 16, 2, 2>, 128, 64},
+    {"128x64x32_w2x2", launch_cfg<128, 64, 32, 2, 2>, 128, 64},
+    {"256x128x16_w4x2", launch_cfg<256, 128, 16, 4, 2>, 256, 128},
+    {"64x64x16_w2x2", launch_cfg<64, 64, 16, 2, 2>, 64, 64},
+    {"64x64x32_w2x2", launch_cfg<64, 64, 32, 2, 2>, 64, 64},
+    {"128x128x16_w4x2", launch_cfg<128, 128, 16, 4, 2>, 128, 128},
+    {"64x128x32_w1x4", launch_cfg<64, 128, 32, 1, 4>, 64, 128},
+    {"64x256x16_w1x4", launch_cfg<64, 256, 16, 1, 4>, 64, 256},
+};
+constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+}  // namespace
+
+// Variant ids: 0 = choose from the shape, 1 .. kNumVariants-1 = register-staged tiles of this file,
+// kNumVariants .. = the persistent direct-to-LDS kernels.
+int gemm_f32_variant_count() { return kNumVariants + gemm_f32_async_variant_count(); }
+const char* gemm_f32_variant_name(int v)
+{
+    if (v >= 0 && v < kNumVariants) return kVariants[v].name;
+    return gemm_f32_async_variant_name(v - kNumVariants);
+}
+
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s)
 {
     if (!p.At || !p.B || !p.D) return hipErrorInvalidValue;
     if (p.M <= 0 || p.Ncols <= 0 || p.R <= 0 || p.batch <= 0 || p.L <= 0) return hipErrorInvalidValue;
     if (p.lda < p.M || (p.lda & 3) || !aligned16(p.At) || (p.strideA_batch & 3)) return hipErrorInvalidValue;
+    if (p.variant < 0 || p.variant >= gemm_f32_variant_count()) return hipErrorInvalidValue;
+    if (p.variant >= kNumVariants) return launch_gemm_f32_async(p, p.variant - kNumVariants, s);
     const bool vec = aligned16(p.B) && (p.L % 4 == 0) && (p.Ncols % 4 == 0) && (p.strideB_batch % 4 == 0) &&
                      (p.strideB_img % 4 == 0) && (p.strideB_row % 4 == 0);
-    if (p.M <= 64) return launch_cfg<64, 128, 16, 1, 4>(p, vec, s);
-    return launch_cfg<128, 128, 16, 2, 2>(p, vec, s);
+    int v = p.variant;
+    if (v == 0) v = (p.M <= 64) ? 2 : 1;
+    return kVariants[v].fn(p, vec, s);
 }
 
 }  // namespace mnnconv

@@ -21,6 +21,11 @@ struct WinoGeom {
     int P;                      // N * th * tw
     int ldp;                    // row length of V / M rows (P rounded up to 4)
     int ldk;                    // row length of U rows (K rounded up to 4)
+    // Blocked ("MFMA-native") layout used by the fused kernel instead of the row layouts
+    // (xi = a*alpha + b):  Ub[b][c/4][a][k/16][c%4][k%16],  Vb[b][c/4][a][p/16][c%4][p%16]
+    int blocked;                // 0: row layouts U[xi][c][ldk], V[xi][c][ldp];  1: blocked
+    int kg, pg;                 // allocated 16-column groups along K and along P
+    int cchunks;                // allocated 4-channel groups (>= ceil(C/4), padded to whole chunks)
 };
 
 // U[xi][c][k] = (G w[k][c] G^T)[xi/alpha][xi%alpha]          (Section 3.3.1, G W G^T)
@@ -37,6 +42,14 @@ hipError_t launch_output_transform(const WinoGeom& g, const float* AT /*host, n 
 
 bool winograd_kernels_available(int n, int k);
 
+// Winograd-domain product with the inverse transform and bias fused in:
+// y = A^T [ sum_c U (.) V ] A + bias, operands in the blocked layout.  M is never stored.
+// config 0: 32 channels x 32 tiles per workgroup; config 1: 64 x 32 (only where wino_fused_has_big_block).
+bool wino_fused_available(int n, int k);
+bool wino_fused_has_big_block(int n, int k);
+hipError_t launch_wino_fused(const WinoGeom& g, int config, const float* AT /*host*/, const float* Ub,
+                             const float* Vb, const float* bias, float* y, hipStream_t s);
+
 // Batched GEMM  D_b[m][col] = sum_r At_b[r][m] * B_b[r][col] (+ bias[m]).
 //   At: [batch][R][lda]  (A stored transposed, m contiguous; lda % 4 == 0, 16-byte aligned)
 //   B : element (r, col) at  B + b*strideB_batch + (col / L)*strideB_img + r*strideB_row + (col % L)
@@ -51,8 +64,16 @@ struct GemmProblem {
     long long strideA_batch;
     long long strideB_batch, strideB_img, strideB_row;
     long long strideD_batch, strideD_img, strideD_row;
+    int variant;                // 0 = choose from the shape; > 0 = a specific tile configuration (tuning, tests)
 };
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s);
+// Persistent variant with direct-to-LDS operand copies (gemm_async.hip); needs 16-byte granules on B.
+bool gemm_f32_async_usable(const GemmProblem& p);
+int gemm_f32_async_variant_count();
+const char* gemm_f32_async_variant_name(int variant);
+hipError_t launch_gemm_f32_async(const GemmProblem& p, int variant, hipStream_t s);
+int gemm_f32_variant_count();
+const char* gemm_f32_variant_name(int variant);
 
 // Wt[r][k] = w[k][r], r < R = C*kh*kw, row length ldk (zero padded)
 hipError_t launch_weight_transpose(const float* w, float* Wt, int K, int R, int ldk, hipStream_t s);

@@ -45,20 +45,35 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(WinoGeom g, Filte
         for (int j = 0; j < a; ++j) {
             float acc = 0.f;
             for (int s = 0; s < k; ++s) acc = fmaf(tmp[i][s], gm.g[j][s], acc);
-            U[((long long)(i * a + j) * g.C + c) * g.ldk + kk] = acc;
+            const int xi = i * a + j;
+            if (g.blocked)   // Ub[b = j][c/4][a = i][k/16][c%4][k%16]
+                U[(((((long long)j * g.cchunks + (c >> 2)) * a + i) * g.kg + (kk >> 4)) << 6) + ((c & 3) << 4) + (kk & 15)] = acc;
+            else
+                U[((long long)xi * g.C + c) * g.ldk + kk] = acc;
         }
 }
 
 // ---------------------------------------------------------------- input: V = B^T d B
-template <int A>
+template <int A, bool BLOCKED>
 __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg<A, A> bt,
                                                               const float* __restrict__ x,
                                                               float* __restrict__ V)
 {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)g.C * g.P) return;
-    const int c = (int)(idx / g.P);
-    const int p = (int)(idx % g.P);
+    int c, p;
+    if constexpr (BLOCKED) {
+        // a wavefront owns 16 consecutive tiles x 4 consecutive channels = one 64-float block per position
+        const int pgroups = (g.P + 15) >> 4;
+        const long long rest = idx >> 6;
+        if (rest >= (long long)g.cchunks * pgroups) return;
+        p = (int)(rest % pgroups) * 16 + (int)(idx & 15);
+        c = (int)(rest / pgroups) * 4 + (int)((idx >> 4) & 3);
+        if (p >= g.P || c >= g.C) return;
+    } else {
+        if (idx >= (long long)g.C * g.P) return;
+        c = (int)(idx / g.P);
+        p = (int)(idx % g.P);
+    }
     const int tx = p % g.tw;
     const int t2 = p / g.tw;
     const int ty = t2 % g.th;
@@ -91,8 +106,18 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg
             t[i][j] = acc;
         }
     // v = t B,  v[i][j] = sum_b t[i][b] B^T[j][b]
-    const long long plane = (long long)g.C * g.ldp;
-    float* vp = V + (long long)c * g.ldp + p;
+    // element (a = i, b = j): row layout V[(i*A + j)][c][p]; blocked layout Vb[j][c/4][i][p/16][c%4][p%16]
+    long long stride_i, stride_j;
+    float* vp;
+    if constexpr (BLOCKED) {
+        stride_i = (long long)g.pg * 64;
+        stride_j = (long long)g.cchunks * A * g.pg * 64;
+        vp = V + (((long long)(c >> 2) * A * g.pg + (p >> 4)) << 6) + ((c & 3) << 4) + (p & 15);
+    } else {
+        stride_j = (long long)g.C * g.ldp;
+        stride_i = stride_j * A;
+        vp = V + (long long)c * g.ldp + p;
+    }
 #pragma unroll
     for (int i = 0; i < A; ++i)
 #pragma unroll
@@ -100,7 +125,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg
             float acc = 0.f;
 #pragma unroll
             for (int b = 0; b < A; ++b) acc = fmaf(t[i][b], bt.v[j][b], acc);
-            vp[(long long)(i * A + j) * plane] = acc;
+            vp[i * stride_i + j * stride_j] = acc;
         }
 }
 
@@ -160,9 +185,15 @@ hipError_t launch_input_t(const WinoGeom& g, const float* BT, const float* x, fl
     MatArg<A, A> m;
     for (int i = 0; i < A; ++i)
         for (int j = 0; j < A; ++j) m.v[i][j] = BT[i * A + j];
-    const long long total = (long long)g.C * g.P;
-    const unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(input_transform_kernel<A>, dim3(blocks), dim3(256), 0, s, g, m, x, V);
+    if (g.blocked) {
+        const long long total = (long long)g.cchunks * ((g.P + 15) / 16) * 64;
+        const unsigned blocks = (unsigned)((total + 255) / 256);
+        hipLaunchKernelGGL((input_transform_kernel<A, true>), dim3(blocks), dim3(256), 0, s, g, m, x, V);
+    } else {
+        const long long total = (long long)g.C * g.P;
+        const unsigned blocks = (unsigned)((total + 255) / 256);
+        hipLaunchKernelGGL((input_transform_kernel<A, false>), dim3(blocks), dim3(256), 0, s, g, m, x, V);
+    }
     return hipGetLastError();
 }
 
@@ -187,7 +218,11 @@ bool geom_ok(const WinoGeom& g)
     if (g.Ho <= 0 || g.Wo <= 0) return false;
     if (g.th != (g.Ho + g.n - 1) / g.n || g.tw != (g.Wo + g.n - 1) / g.n) return false;
     if ((long long)g.P != (long long)g.N * g.th * g.tw) return false;
-    if (g.ldp < g.P || g.ldk < g.K) return false;
+    if (g.blocked) {
+        if ((long long)g.cchunks * 4 < g.C || (long long)g.kg * 16 < g.K || (long long)g.pg * 16 < g.P) return false;
+    } else if (g.ldp < g.P || g.ldk < g.K) {
+        return false;
+    }
     // every per-plane element count must fit the 32-bit tile arithmetic used in the kernels
     if ((long long)g.C * g.ldp >= (1ll << 31) || (long long)g.K * g.ldp >= (1ll << 31)) return false;
     if ((long long)g.H * g.W >= (1ll << 31)) return false;

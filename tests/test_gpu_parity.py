@@ -31,7 +31,8 @@ def forced_options(layer):
     out = []
     for s in m.enumerate_schemes(layer.n, layer.c_in, layer.h, layer.w, layer.c_out, layer.kh, layer.kw,
                                  stride=layer.stride, pad=layer.pad, dil=layer.dil):
-        out.append((s.label(layer.kh), m.Options(force_kind=s.kind, force_tile_n=s.tile_n, force_prec=s.prec)))
+        out.append((s.label(layer.kh), m.Options(force_kind=s.kind, force_tile_n=s.tile_n, force_prec=s.prec,
+                                                 force_variant=s.variant)))
     return out
 
 
