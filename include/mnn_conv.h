@@ -85,7 +85,8 @@ typedef struct {
     int32_t force_prec;       /* mnn_gemm_prec used for forced schemes                    */
     int32_t force_variant;    /* MNN_WINO_* used for a forced Winograd scheme; -1 = time the variants */
     int32_t allow_bf16;       /* 1: AUTO may also time bf16 candidates                    */
-    int32_t alpha_max;        /* largest n + k - 1 the planner may generate (default 8, max 12) */
+    int32_t alpha_max;        /* largest n + k - 1 the planner may generate (default 8, max 10:
+                                 beyond that the fp32 error of the transforms exceeds 1e-3)          */
     float   point_scale_f;    /* f of the Winograd generator (default 0.5)                */
     int32_t plan_warmup;      /* untimed launches per candidate (default 2)               */
     int32_t plan_iters;       /* timed launches per candidate (default 10)                */
@@ -183,6 +184,10 @@ int mnn_conv_invalidate_weights(mnn_conv_plan_t plan);
 /* Device address and size in bytes of one of the plan's buffers (MNN_BUF_*);
  * *ptr is NULL when the scheme has no such buffer. */
 int mnn_conv_plan_buffer(mnn_conv_plan_t plan, int32_t which, void** ptr, size_t* bytes);
+
+/* Copies one of the plan's buffers to host memory after synchronising `stream` (inspection, tests).
+ * dst: host, at least `bytes` bytes; bytes must not exceed the buffer size. */
+int mnn_conv_read_buffer(mnn_conv_plan_t plan, int32_t which, void* dst, size_t bytes, void* stream);
 
 void mnn_conv_plan_destroy(mnn_conv_plan_t plan);
 

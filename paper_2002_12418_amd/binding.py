@@ -81,6 +81,7 @@ def _load() -> ctypes.CDLL:
     L.mnn_conv_run_stage.argtypes = [vp, c_int32, vp, vp, vp, vp, vp]
     L.mnn_conv_invalidate_weights.argtypes = [vp]
     L.mnn_conv_plan_buffer.argtypes = [vp, c_int32, POINTER(vp), POINTER(c_size_t)]
+    L.mnn_conv_read_buffer.argtypes = [vp, c_int32, vp, c_size_t, vp]
     L.mnn_conv_plan_destroy.argtypes = [vp]
     L.mnn_conv_plan_destroy.restype = None
     L.mnn_conv_get_transforms.argtypes = [c_int32, c_int32, c_float, vp, vp, vp]
@@ -325,19 +326,14 @@ class ConvPlan:
         _check(lib.mnn_conv_plan_buffer(self._h, which, byref(p), byref(nbytes)))
         return (p.value or 0), int(nbytes.value)
 
-    def buffer_to_numpy(self, which: int) -> Optional[np.ndarray]:
+    def buffer_to_numpy(self, which: int, stream=None) -> Optional[np.ndarray]:
         """Copy one of the plan's device buffers to the host as a flat float32 array (test helper)."""
-        import torch
         ptr, nbytes = self.buffer(which)
         if not ptr:
             return None
-        torch.cuda.synchronize()
-        out = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda")
-        rc = torch.cuda.cudart().cudaMemcpy(out.data_ptr(), ptr, nbytes, 3)  # device-to-device
-        if int(rc) != 0:
-            raise RuntimeError(f"memcpy of plan buffer failed ({rc})")
-        torch.cuda.synchronize()
-        return out.cpu().numpy()
+        out = np.empty(nbytes // 4, dtype=np.float32)
+        _check(lib.mnn_conv_read_buffer(self._h, which, out.ctypes.data, nbytes, _stream_handle(stream)))
+        return out
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:

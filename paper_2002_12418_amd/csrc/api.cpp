@@ -92,7 +92,8 @@ int validate_options(const mnn_conv_options* in, mnn_conv_options* o)
 {
     if (in) *o = *in; else default_options(o);
     if (o->alpha_max <= 0) o->alpha_max = 8;
-    if (o->alpha_max > kMaxAlpha) return fail(MNN_E_UNSUPPORTED, "alpha_max above %d", kMaxAlpha);
+    if (o->alpha_max > kMaxAlphaT)
+        return fail(MNN_E_UNSUPPORTED, "alpha_max above %d: the fp32 error of larger tiles exceeds 1e-3", kMaxAlphaT);
     if (!(o->point_scale_f > 0.f)) return fail(MNN_E_INVALID_ARG, "point_scale_f must be positive");
     if (o->plan_warmup < 0 || o->plan_iters <= 0) return fail(MNN_E_INVALID_ARG, "plan_warmup >= 0 and plan_iters > 0 required");
     if (o->force_kind < MNN_SCHEME_AUTO || o->force_kind > MNN_SCHEME_GEMM1X1)
@@ -203,7 +204,9 @@ std::map<GemmKey, int> g_gemm_choice;
 GemmKey gemm_key(int device, const GemmProblem& p)
 {
     std::vector<long long> v = {p.M, p.Ncols, p.R, p.batch, p.lda, p.L, p.strideA_batch, p.strideB_batch, p.strideB_img,
-                                p.strideB_row, p.strideD_batch, p.strideD_img, p.strideD_row, p.bias ? 1 : 0};
+                                p.strideB_row, p.strideD_batch, p.strideD_img, p.strideD_row, p.bias ? 1 : 0,
+                                p.gather, p.cv_C, p.cv_H, p.cv_W, p.cv_kh, p.cv_kw, p.cv_sh, p.cv_sw, p.cv_ph, p.cv_pw,
+                                p.cv_dh, p.cv_dw, p.cv_Wo};
     return GemmKey(device, v);
 }
 
@@ -298,8 +301,8 @@ struct Impl {
         if (s.kind == MNN_SCHEME_WINOGRAD) {
             if (!winograd_admissible(L)) return fail(MNN_E_UNSUPPORTED, "Winograd needs a square kernel >= 2, stride 1, dilation 1");
             const int n = s.tile_n, k = sh.kh;
-            if (!winograd_kernels_available(n, k) || n + k - 1 > kMaxAlpha)
-                return fail(MNN_E_UNSUPPORTED, "F(%d,%d) is outside the built range (n 2..8, k 2..7, alpha <= %d)", n, k, kMaxAlpha);
+            if (!winograd_kernels_available(n, k))
+                return fail(MNN_E_UNSUPPORTED, "F(%d,%d) is outside the built range (n 2..8, k 2..7, alpha <= %d)", n, k, kMaxAlphaT);
             if (!generate_winograd(n, k, (double)o.point_scale_f, &mats))
                 return fail(MNN_E_UNSUPPORTED, "generator rejected F(%d,%d)", n, k);
             wg.N = sh.n; wg.C = sh.c_in; wg.H = sh.h; wg.W = sh.w; wg.K = sh.c_out;
@@ -344,6 +347,12 @@ struct Impl {
             return alloc_zero(&U, U_bytes, "hipMalloc Wt");
         }
         if (s.kind == MNN_SCHEME_DIRECT) {
+            // implicit GEMM on the matrix cores: weights transposed to [C*kh*kw][ldk]
+            if ((long long)sh.n * L.Ho * L.Wo >= (1ll << 31) || (long long)sh.n * sh.c_in * sh.h * sh.w >= (1ll << 31))
+                return fail(MNN_E_UNSUPPORTED, "tensor too large for the sliding-window kernel");
+            U_bytes = (size_t)sh.c_in * sh.kh * sh.kw * ldk * sizeof(float);
+            int rcd = alloc_zero(&U, U_bytes, "hipMalloc Wt");
+            if (rcd) return rcd;
             dg.N = sh.n; dg.C = sh.c_in; dg.H = sh.h; dg.W = sh.w; dg.K = sh.c_out; dg.kh = sh.kh; dg.kw = sh.kw;
             dg.Ho = L.Ho; dg.Wo = L.Wo;
             dg.stride_h = L.g.stride_h; dg.stride_w = L.g.stride_w; dg.pad_h = L.g.pad_h; dg.pad_w = L.g.pad_w;
@@ -381,16 +390,33 @@ struct Impl {
         return p;
     }
 
+    GemmProblem direct_gemm_problem(const float* x, const float* b, float* y) const
+    {
+        const mnn_conv_shape& sh = L.s;
+        const int HoWo = L.Ho * L.Wo;
+        GemmProblem p{};
+        p.At = U; p.B = x; p.D = y; p.bias = b;
+        p.M = sh.c_out; p.Ncols = sh.n * HoWo; p.R = sh.c_in * sh.kh * sh.kw; p.batch = 1;
+        p.lda = ldk; p.L = HoWo;
+        p.strideD_img = (long long)sh.c_out * HoWo; p.strideD_row = HoWo;
+        p.variant = gemm_variant;
+        p.gather = 1;
+        p.cv_C = sh.c_in; p.cv_H = sh.h; p.cv_W = sh.w; p.cv_kh = sh.kh; p.cv_kw = sh.kw;
+        p.cv_sh = L.g.stride_h; p.cv_sw = L.g.stride_w; p.cv_ph = L.g.pad_h; p.cv_pw = L.g.pad_w;
+        p.cv_dh = L.g.dil_h; p.cv_dw = L.g.dil_w; p.cv_Wo = L.Wo;
+        return p;
+    }
+
     // Picks the GEMM tile configuration by timing (pre-inference).  The 1x1 scheme multiplies the
     // caller's tensors, so it is tuned on scratch tensors of the layer's size.
     int tune(hipStream_t s)
     {
         if (scheme.kind == MNN_SCHEME_WINOGRAD && scheme.variant == MNN_WINO_UNFUSED)
             return tune_gemm(wino_gemm_problem(), s, &gemm_variant);
-        if (scheme.kind == MNN_SCHEME_GEMM1X1) {
+        if (scheme.kind == MNN_SCHEME_GEMM1X1 || scheme.kind == MNN_SCHEME_DIRECT) {
             const mnn_conv_shape& sh = L.s;
             const size_t xb = (size_t)sh.n * sh.c_in * sh.h * sh.w * sizeof(float);
-            const size_t yb = (size_t)sh.n * sh.c_out * sh.h * sh.w * sizeof(float);
+            const size_t yb = (size_t)sh.n * sh.c_out * L.Ho * L.Wo * sizeof(float);
             float *tx = nullptr, *ty = nullptr, *tb = nullptr;
             hipError_t e;
             int rc = MNN_OK;
@@ -399,7 +425,9 @@ struct Impl {
                 rc = fail_hip(e, "hipMalloc tuning scratch");
             if (!rc && ((e = hipMemset(tx, 0, xb)) != hipSuccess || (e = hipMemset(tb, 0, (size_t)sh.c_out * sizeof(float))) != hipSuccess))
                 rc = fail_hip(e, "hipMemset tuning scratch");
-            if (!rc) rc = tune_gemm(pointwise_gemm_problem(tx, tb, ty), s, &gemm_variant);
+            if (!rc)
+                rc = tune_gemm(scheme.kind == MNN_SCHEME_DIRECT ? direct_gemm_problem(tx, tb, ty)
+                                                                : pointwise_gemm_problem(tx, tb, ty), s, &gemm_variant);
             if (tx) (void)hipFree(tx);
             if (ty) (void)hipFree(ty);
             if (tb) (void)hipFree(tb);
@@ -413,7 +441,7 @@ struct Impl {
         switch (scheme.kind) {
             case MNN_SCHEME_WINOGRAD: return scheme.variant == MNN_WINO_UNFUSED || st != MNN_STAGE_OUTPUT;
             case MNN_SCHEME_GEMM1X1: return st == MNN_STAGE_FILTER || st == MNN_STAGE_GEMM;
-            default: return st == MNN_STAGE_GEMM;
+            default: return st == MNN_STAGE_FILTER || st == MNN_STAGE_GEMM;
         }
     }
 
@@ -444,7 +472,10 @@ struct Impl {
                 e = launch_gemm_f32(pointwise_gemm_problem(x, b, y), s);
             }
         } else {
-            e = launch_direct_conv(dg, x, w, b, y, s);
+            if (st == MNN_STAGE_FILTER)
+                e = launch_weight_transpose(w, U, sh.c_out, sh.c_in * sh.kh * sh.kw, ldk, s);
+            else
+                e = launch_gemm_f32(direct_gemm_problem(x, b, y), s);
         }
         if (e != hipSuccess) return fail_hip(e, "kernel launch");
         return MNN_OK;
@@ -776,6 +807,20 @@ int mnn_conv_plan_buffer(mnn_conv_plan_t plan, int32_t which, void** ptr, size_t
     return MNN_OK;
 }
 
+int mnn_conv_read_buffer(mnn_conv_plan_t plan, int32_t which, void* dst, size_t bytes, void* stream)
+{
+    void* src = nullptr;
+    size_t have = 0;
+    int rc = mnn_conv_plan_buffer(plan, which, &src, &have);
+    if (rc) return rc;
+    if (!dst) return fail(MNN_E_INVALID_ARG, "dst is NULL");
+    if (!src || bytes > have) return fail(MNN_E_INVALID_ARG, "the plan has no such buffer or it is smaller than %zu bytes", bytes);
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+    if ((e = hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost)) != hipSuccess) return fail_hip(e, "hipMemcpy");
+    return MNN_OK;
+}
+
 void mnn_conv_plan_destroy(mnn_conv_plan_t plan) { delete plan; }
 
 int mnn_conv_get_transforms(int32_t n, int32_t k, float f, float* AT, float* G, float* BT)
@@ -785,7 +830,7 @@ int mnn_conv_get_transforms(int32_t n, int32_t k, float f, float* AT, float* G, 
     WinogradMatrices m;
     try {
         if (!generate_winograd(n, k, (double)f, &m))
-            return fail(MNN_E_UNSUPPORTED, "F(%d,%d): alpha = %d is outside 2..%d", n, k, n + k - 1, kMaxAlpha);
+            return fail(MNN_E_UNSUPPORTED, "F(%d,%d): alpha = %d is outside 2..%d", n, k, n + k - 1, kMaxAlpha);  // the generator itself goes further than the kernels
     } catch (...) {
         return fail(MNN_E_OOM, "host allocation failed");
     }

@@ -38,7 +38,9 @@ __device__ __forceinline__ int xcd_remap(int bid, int total)
     return xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool VEC>
+// MODE 0: B read element by element through the (col / L, col % L) mapping; 1: the same with 16-byte
+// loads; 2: B gathered from an NCHW tensor (implicit GEMM of the sliding-window convolution).
+template <int BM, int BN, int BK, int WM, int WN, int MODE>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, int tilesM, int tilesN, int total)
 {
     constexpr int NT = WM * WN * 64;
@@ -79,9 +81,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
         a_col[j] = (s % (BM / 4)) * 4;
         a_ok[j] = (m0 + a_col[j]) < p.lda;
     }
+    constexpr bool VEC = (MODE == 1);
     int b_row[LB], b_col[LB];
     long long b_off[LB][VEC ? 1 : 4];
     bool b_ok[LB][VEC ? 1 : 4];
+    int g_y[LB][MODE == 2 ? 4 : 1], g_x[LB][MODE == 2 ? 4 : 1];   // gather: top-left input coordinate of the column
 #pragma unroll
     for (int j = 0; j < LB; ++j) {
         const int s = tid + j * NT;
@@ -92,7 +96,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
             const int col = n0 + b_col[j] + e;
             b_ok[j][e] = col < p.Ncols;
             const int img = col / p.L, rest = col % p.L;
-            b_off[j][e] = (long long)img * p.strideB_img + rest;
+            if constexpr (MODE == 2) {
+                b_off[j][e] = (long long)img * p.cv_C * p.cv_H * p.cv_W;
+                g_y[j][e] = (rest / p.cv_Wo) * p.cv_sh - p.cv_ph;
+                g_x[j][e] = (rest % p.cv_Wo) * p.cv_sw - p.cv_pw;
+            } else {
+                b_off[j][e] = (long long)img * p.strideB_img + rest;
+            }
         }
     }
 
@@ -110,6 +120,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
         for (int j = 0; j < LB; ++j) {
             const int r = r0 + b_row[j];
             const bool rok = r < p.R;
+            if constexpr (MODE == 2) {
+                const int taps = p.cv_kh * p.cv_kw;
+                const int c = r / taps, rem = r % taps;
+                const int dy = (rem / p.cv_kw) * p.cv_dh, dx = (rem % p.cv_kw) * p.cv_dw;
+                const float* plane = Bb + (long long)c * p.cv_H * p.cv_W;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int iy = g_y[j][e] + dy, ix = g_x[j][e] + dx;
+                    const bool ok = rok && b_ok[j][e] && iy >= 0 && iy < p.cv_H && ix >= 0 && ix < p.cv_W;
+                    v[e] = ok ? plane[b_off[j][e] + (long long)iy * p.cv_W + ix] : 0.f;
+                }
+                rb[j] = make_float4(v[0], v[1], v[2], v[3]);
+                continue;
+            }
             const float* rowp = Bb + (long long)r * p.strideB_row;
             if constexpr (VEC) {
                 if (rok && b_ok[j][0])
@@ -199,11 +224,14 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
     const int tilesN = (p.Ncols + BN - 1) / BN;
     const long long total = (long long)tilesM * tilesN * p.batch;
     if (total <= 0 || total >= (1ll << 31)) return hipErrorInvalidValue;
-    if (vec)
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, true>), dim3((unsigned)total), dim3(WM * WN * 64),
+    if (p.gather)
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2>), dim3((unsigned)total), dim3(WM * WN * 64),
+                           0, s, p, tilesM, tilesN, (int)total);
+    else if (vec)
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1>), dim3((unsigned)total), dim3(WM * WN * 64),
                            0, s, p, tilesM, tilesN, (int)total);
     else
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, false>), dim3((unsigned)total), dim3(WM * WN * 64),
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0>), dim3((unsigned)total), dim3(WM * WN * 64),
                            0, s, p, tilesM, tilesN, (int)total);
     return hipGetLastError();
 }
@@ -246,6 +274,12 @@ hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s)
     if (p.M <= 0 || p.Ncols <= 0 || p.R <= 0 || p.batch <= 0 || p.L <= 0) return hipErrorInvalidValue;
     if (p.lda < p.M || (p.lda & 3) || !aligned16(p.At) || (p.strideA_batch & 3)) return hipErrorInvalidValue;
     if (p.variant < 0 || p.variant >= gemm_f32_variant_count()) return hipErrorInvalidValue;
+    if (p.gather) {
+        if (p.cv_C <= 0 || p.cv_H <= 0 || p.cv_W <= 0 || p.cv_kh <= 0 || p.cv_kw <= 0 || p.cv_sh <= 0 || p.cv_sw <= 0 ||
+            p.cv_dh <= 0 || p.cv_dw <= 0 || p.cv_Wo <= 0 || p.L % p.cv_Wo != 0 || p.R != p.cv_C * p.cv_kh * p.cv_kw)
+            return hipErrorInvalidValue;
+        if (p.variant >= kNumVariants) return hipErrorInvalidValue;   // the direct-to-LDS kernels cannot gather
+    }
     if (p.variant >= kNumVariants) return launch_gemm_f32_async(p, p.variant - kNumVariants, s);
     const bool vec = aligned16(p.B) && (p.L % 4 == 0) && (p.Ncols % 4 == 0) && (p.strideB_batch % 4 == 0) &&
                      (p.strideB_img % 4 == 0) && (p.strideB_row % 4 == 0);

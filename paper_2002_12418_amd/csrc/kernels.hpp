@@ -6,7 +6,10 @@
 
 namespace mnnconv {
 
-constexpr int kMaxAlphaT = 12;   // largest alpha = n + k - 1 the transform kernels are built for
+// Largest alpha = n + k - 1 the Winograd kernels are built for.  In fp32 the error of the generated
+// transforms grows quickly with alpha: about 3e-4 of the output range at alpha = 10 and above 1e-2 from
+// alpha = 11 on, which is outside the accuracy this library promises.
+constexpr int kMaxAlphaT = 10;
 
 // Transform matrix handed to kernels by value (lands in SGPRs).
 template <int R, int C>
@@ -65,6 +68,11 @@ struct GemmProblem {
     long long strideB_batch, strideB_img, strideB_row;
     long long strideD_batch, strideD_img, strideD_row;
     int variant;                // 0 = choose from the shape; > 0 = a specific tile configuration (tuning, tests)
+    // Implicit-GEMM gather for the sliding-window scheme (gather != 0): B is the input tensor x[N][C][H][W],
+    // row r = (c, kr, ks), column = (img, oy, ox), element = x[img][c][oy*sh - ph + kr*dh][ox*sw - pw + ks*dw] or 0.
+    // L must be H_o*W_o; the strideB_* fields are ignored.
+    int gather;
+    int cv_C, cv_H, cv_W, cv_kh, cv_kw, cv_sh, cv_sw, cv_ph, cv_pw, cv_dh, cv_dw, cv_Wo;
 };
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s);
 // Persistent variant with direct-to-LDS operand copies (gemm_async.hip); needs 16-byte granules on B.

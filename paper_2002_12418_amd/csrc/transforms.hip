@@ -255,7 +255,7 @@ hipError_t launch_input_transform(const WinoGeom& g, const float* BT, const floa
     switch (g.alpha) {
 #define MNN_CASE(A) case A: return launch_input_t<A>(g, BT, x, V, s);
         MNN_CASE(3) MNN_CASE(4) MNN_CASE(5) MNN_CASE(6) MNN_CASE(7) MNN_CASE(8)
-        MNN_CASE(9) MNN_CASE(10) MNN_CASE(11) MNN_CASE(12)
+        MNN_CASE(9) MNN_CASE(10)
 #undef MNN_CASE
         default: return hipErrorInvalidValue;
     }
@@ -268,11 +268,13 @@ hipError_t launch_output_transform(const WinoGeom& g, const float* AT, const flo
     if (!winograd_kernels_available(g.n, g.k)) return hipErrorInvalidValue;
 #define MNN_NK(NN, KK) \
     if (g.n == NN && g.k == KK) return launch_output_t<NN, NN + KK - 1>(g, AT, M, bias, y, s);
-#define MNN_N(NN) MNN_NK(NN, 2) MNN_NK(NN, 3) MNN_NK(NN, 4) MNN_NK(NN, 5)
-    MNN_N(2) MNN_N(3) MNN_N(4) MNN_N(5) MNN_N(6) MNN_N(7) MNN_N(8)
-    MNN_NK(2, 6) MNN_NK(3, 6) MNN_NK(4, 6) MNN_NK(5, 6) MNN_NK(6, 6) MNN_NK(7, 6)
-    MNN_NK(2, 7) MNN_NK(3, 7) MNN_NK(4, 7) MNN_NK(5, 7) MNN_NK(6, 7)
-#undef MNN_N
+    // every (n, k) with 2 <= n <= 8, 2 <= k <= 7 and n + k - 1 <= 10
+    MNN_NK(2, 2) MNN_NK(3, 2) MNN_NK(4, 2) MNN_NK(5, 2) MNN_NK(6, 2) MNN_NK(7, 2) MNN_NK(8, 2)
+    MNN_NK(2, 3) MNN_NK(3, 3) MNN_NK(4, 3) MNN_NK(5, 3) MNN_NK(6, 3) MNN_NK(7, 3) MNN_NK(8, 3)
+    MNN_NK(2, 4) MNN_NK(3, 4) MNN_NK(4, 4) MNN_NK(5, 4) MNN_NK(6, 4) MNN_NK(7, 4)
+    MNN_NK(2, 5) MNN_NK(3, 5) MNN_NK(4, 5) MNN_NK(5, 5) MNN_NK(6, 5)
+    MNN_NK(2, 6) MNN_NK(3, 6) MNN_NK(4, 6) MNN_NK(5, 6)
+    MNN_NK(2, 7) MNN_NK(3, 7) MNN_NK(4, 7)
 #undef MNN_NK
     return hipErrorInvalidValue;
 }

@@ -1,0 +1,175 @@
+"""Host-side checks of the C ABI (no GPU needed): exports, generator, analytic cost, candidate
+enumeration, the selection rule and argument validation."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import cook_toom, cost_model
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def mnn():
+    import paper_2002_12418_amd as m
+    m.lib  # forces the load; raises if the shared object is missing and cannot be built
+    return m
+
+
+def test_every_declared_symbol_is_exported(mnn):
+    header = open(os.path.join(ROOT, "include", "mnn_conv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = sorted(set(re.findall(r"\b(mnn_[a-z0-9_]+)\s*\(", header)))
+    assert len(names) >= 20
+    lib = ctypes.CDLL(mnn.library_path())
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in mnn_conv.h but not exported"
+
+
+def test_version_and_defaults(mnn):
+    assert mnn.version() >= 100
+    o = mnn.Options.defaults()
+    assert (o.force_kind, o.alpha_max, o.plan_iters, o.use_cache, o.force_variant) == (mnn.SCHEME_AUTO, 8, 10, 1, -1)
+    assert o.point_scale_f == 0.5
+
+
+NK = [(n, k) for k in range(2, 8) for n in range(2, 9) if n + k - 1 <= 12]
+
+
+@pytest.mark.parametrize("n,k", NK)
+@pytest.mark.parametrize("f", [0.5, 1.0, 0.25])
+def test_generator_equals_exact_rationals_rounded_once(mnn, n, k, f):
+    """The library's host generator (integer symmetric polynomials times powers of f) against the oracle's
+    independent exact-rational construction: identical float32 matrices."""
+    from fractions import Fraction
+    AT, G, BT = mnn.get_transforms(n, k, f)
+    AT_q, G_q, BT_q = cook_toom.matrices(n, k, Fraction(f))
+    for got, want in ((AT, AT_q), (G, G_q), (BT, BT_q)):
+        want32 = cook_toom.to_float(want).astype(np.float32)
+        assert got.shape == want32.shape
+        np.testing.assert_array_equal(got, want32)
+
+
+def test_generator_rejects_bad_arguments(mnn):
+    with pytest.raises(mnn.MnnError) as e:
+        mnn.get_transforms(8, 7, 0.5)           # alpha = 14 > 12
+    assert e.value.code == -2
+    with pytest.raises(mnn.MnnError) as e:
+        mnn.get_transforms(2, 3, -1.0)
+    assert e.value.code == -1
+
+
+@pytest.mark.parametrize("shape", [(3, 64, 64, 56, 56), (3, 512, 512, 7, 7), (5, 128, 128, 64, 64), (7, 64, 64, 112, 112),
+                                   (2, 3, 16, 223, 223), (3, 16, 16, 32, 32)])
+def test_analytic_cost_matches_oracle_model(mnn, shape):
+    k, ic, oc, oh, ow = shape
+    for n in range(1, 9 - k + 1):
+        assert mnn.analytic_cost(k, ic, oc, oh, ow, n) == float(cost_model.plane_cost(n, k, ic, oc, oh, ow))
+    for amax in (8, 6, 10):
+        if amax >= k:
+            assert mnn.analytic_tile(k, ic, oc, oh, ow, amax) == cost_model.best_tile(k, ic, oc, oh, ow, amax)
+
+
+def test_enumeration_rules(mnn):
+    # k = 1, stride 1, no padding -> one matrix multiplication
+    c = mnn.enumerate_schemes(16, 32, 112, 112, 64, 1, 1)
+    assert [s.kind for s in c] == [mnn.SCHEME_GEMM1X1]
+    # stride 2 / dilation 2 / rectangular kernel -> sliding window only
+    for kw in (dict(stride=2, pad=1), dict(dil=2, pad=2)):
+        c = mnn.enumerate_schemes(1, 64, 56, 56, 128, 3, 3, **kw)
+        assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
+    c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 1, 7)
+    assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
+    # 3x3 stride 1: sliding window + F(n,3) for n = 2..6 (alpha <= 8), each in its kernel arrangements
+    c = mnn.enumerate_schemes(1, 64, 56, 56, 64, 3, 3, pad=1)
+    assert c[0].kind == mnn.SCHEME_DIRECT
+    wino = [s for s in c if s.kind == mnn.SCHEME_WINOGRAD]
+    assert sorted({s.tile_n for s in wino}) == [2, 3, 4, 5, 6]
+    assert all(any(s.tile_n == n and s.variant == mnn.WINO_UNFUSED for s in wino) for n in range(2, 7))
+    assert all(s.est_ms < 0 for s in c)
+    # alpha_max caps n; 7x7 with alpha <= 8 only admits n = 2
+    c = mnn.enumerate_schemes(1, 64, 56, 56, 64, 3, 3, pad=1, options=mnn.Options(alpha_max=6))
+    assert sorted({s.tile_n for s in c if s.kind == mnn.SCHEME_WINOGRAD}) == [2, 3, 4]
+    c = mnn.enumerate_schemes(16, 64, 112, 112, 64, 7, 7, pad=3)
+    assert sorted({s.tile_n for s in c if s.kind == mnn.SCHEME_WINOGRAD}) == [2]
+    # 1x1 with padding is not the plain GEMM case
+    c = mnn.enumerate_schemes(1, 8, 8, 8, 8, 1, 1, pad=1)
+    assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
+
+
+def test_selection_rule(mnn):
+    S = mnn.Scheme
+    W, D = mnn.SCHEME_WINOGRAD, mnn.SCHEME_DIRECT
+    # plain argmin
+    c = [S(D, 0, 0, 0, 1.0), S(W, 2, 0, 0, 0.5), S(W, 4, 0, 0, 0.3), S(W, 6, 0, 0, 0.4)]
+    assert mnn.select_scheme(c, 3) == 2
+    # within 2 % of the best: the smaller alpha wins
+    c = [S(D, 0, 0, 0, 1.0), S(W, 2, 0, 0, 0.303), S(W, 4, 0, 0, 0.300), S(W, 6, 0, 0, 0.301)]
+    assert mnn.select_scheme(c, 3) == 1
+    # ... but not beyond 2 %
+    c = [S(W, 2, 0, 0, 0.310), S(W, 4, 0, 0, 0.300)]
+    assert mnn.select_scheme(c, 3) == 1
+    # untimed candidates are ignored; sliding window counts as alpha = k
+    c = [S(D, 0, 0, 0, 0.2), S(W, 2, 0, 0, -1.0), S(W, 4, 0, 0, 0.2)]
+    assert mnn.select_scheme(c, 3) == 0
+    # same alpha: fp32 before bf16, then the faster arrangement
+    c = [S(W, 4, 1, 0, 0.100), S(W, 4, 0, 1, 0.1005), S(W, 4, 0, 0, 0.101)]
+    assert mnn.select_scheme(c, 3) == 1
+    with pytest.raises(mnn.MnnError):
+        mnn.select_scheme([S(W, 2, 0, 0, -1.0)], 3)
+
+
+def test_selection_is_deterministic(mnn):
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        c = [mnn.Scheme(mnn.SCHEME_WINOGRAD, int(n), 0, int(v), float(t))
+             for n, v, t in zip(rng.integers(2, 7, 8), rng.integers(0, 3, 8), rng.uniform(0.1, 0.2, 8))]
+        first = mnn.select_scheme(c, 3)
+        assert all(mnn.select_scheme(c, 3) == first for _ in range(3))
+        best = min(s.est_ms for s in c)
+        assert c[first].est_ms <= best * 1.02 * (1 + 1e-6)
+
+
+def test_plan_argument_validation(mnn):
+    import torch
+    bad = [
+        dict(n=0, c_in=1, h=4, w=4, c_out=1, kh=3, kw=3),            # empty batch
+        dict(n=1, c_in=1, h=2, w=2, c_out=1, kh=3, kw=3),            # kernel larger than the image
+        dict(n=1, c_in=1, h=4, w=4, c_out=1, kh=3, kw=3, stride=0),
+        dict(n=1, c_in=1, h=4, w=4, c_out=1, kh=3, kw=3, pad=-1),
+    ]
+    for kw in bad:
+        with pytest.raises(mnn.MnnError) as e:
+            mnn.ConvPlan(**kw)
+        assert e.value.code == -1, kw
+    with pytest.raises(mnn.MnnError) as e:
+        mnn.enumerate_schemes(1, 8, 8, 8, 8, 3, 3, options=mnn.Options(alpha_max=11))
+    assert e.value.code == -2
+    if not torch.cuda.is_available():
+        with pytest.raises(mnn.MnnError) as e:
+            mnn.ConvPlan(1, 4, 8, 8, 4, 3, 3, pad=1)
+        assert e.value.code == -5                                     # MNN_E_NO_DEVICE, never a CPU fallback
+        assert "device" in str(e.value).lower()
+
+
+def test_gemm_variant_table(mnn):
+    names = mnn.gemm_variants()
+    assert names[0] == "auto" and len(names) == len(set(names)) and len(names) > 4
+
+
+def test_product_path_does_not_import_the_oracle():
+    """The package, bench hot path and C sources must not reference the oracle."""
+    pkg = os.path.join(ROOT, "paper_2002_12418_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "oracle/" not in text, f
+    for dirpath, _, files in os.walk(os.path.join(ROOT, "oracle")):
+        for f in files:
+            if f.endswith((".py", ".c")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "paper_2002_12418_amd" not in text and "mnn_conv" not in text, f

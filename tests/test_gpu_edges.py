@@ -1,0 +1,102 @@
+"""Edge cases through the C ABI: guard bands around the output, unaligned tensor bases, batch 1,
+one channel, pad 0, outputs smaller than one tile, alpha up to 12, point scale f."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from conv_workloads import ConvLayer, draw, BASE_SEED
+
+pytestmark = pytest.mark.gpu
+
+
+def mnn():
+    import paper_2002_12418_amd as m
+    return m
+
+
+def all_forced(m, layer, **kw):
+    out = []
+    for s in m.enumerate_schemes(layer.n, layer.c_in, layer.h, layer.w, layer.c_out, layer.kh, layer.kw,
+                                 stride=layer.stride, pad=layer.pad, dil=layer.dil, options=m.Options(**kw) if kw else None):
+        out.append((s, m.Options(force_kind=s.kind, force_tile_n=s.tile_n, force_prec=s.prec, force_variant=s.variant, **kw)))
+    return out
+
+
+def tol_for(s, k, m):
+    return 1e-3 if (s.kind == m.SCHEME_WINOGRAD and s.tile_n + k - 1 > 6) else 1e-4
+
+
+LAYERS = [
+    ConvLayer("one_tile", 1, 3, 4, 4, 5, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 801),
+    ConvLayer("single_channel", 2, 1, 10, 11, 1, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 802),
+    ConvLayer("odd_everything", 3, 7, 13, 17, 19, 3, 3, 1, 0, 1, (-1.0, 1.0), BASE_SEED + 803),
+    ConvLayer("pw_odd", 2, 5, 7, 7, 9, 1, 1, 1, 0, 1, (0.0, 1.0), BASE_SEED + 804),
+    ConvLayer("k2", 1, 6, 12, 12, 10, 2, 2, 1, 0, 1, (-1.0, 1.0), BASE_SEED + 805),
+    ConvLayer("s2d2", 2, 6, 15, 14, 10, 3, 3, 2, 2, 2, (-1.0, 1.0), BASE_SEED + 806),
+]
+
+
+@pytest.mark.parametrize("layer", LAYERS, ids=lambda l: l.name)
+@pytest.mark.parametrize("shift", [0, 1])
+def test_guard_bands_and_unaligned_bases(layer, shift):
+    """Output sits inside a larger buffer filled with a canary; shift = 1 also makes every tensor base
+    4-byte instead of 16-byte aligned, which must take the element-wise paths."""
+    m = mnn()
+    x, w, b = draw(layer)
+    ref = oracle.conv2d(x, w, b, stride=layer.stride, pad=layer.pad, dil=layer.dil)
+    guard = 64 + shift
+
+    def place(a):
+        buf = torch.full((a.size + 2 * guard,), 777.0, device="cuda")
+        view = buf[guard:guard + a.size].view(a.shape)
+        view.copy_(torch.from_numpy(a))
+        return buf, view
+
+    (_, xd), (_, wd), (_, bd) = place(x), place(w), place(b)
+    for s, opt in all_forced(m, layer):
+        print(f"[case] {layer.name} shift={shift} {s.label(layer.kh)}", flush=True)
+        ybuf = torch.full((ref.size + 2 * guard,), 777.0, device="cuda")
+        y = ybuf[guard:guard + ref.size].view(ref.shape)
+        with m.ConvPlan.for_layer(layer, options=opt) as plan:
+            plan.run(xd, wd, bd, y)
+            torch.cuda.synchronize()
+        host = ybuf.cpu().numpy()
+        assert np.all(host[:guard] == 777.0) and np.all(host[guard + ref.size:] == 777.0), "wrote outside the output"
+        assert oracle.error_ratio(host[guard:guard + ref.size].reshape(ref.shape), ref) <= tol_for(s, layer.kh, m)
+
+
+def test_large_alpha_and_point_scale():
+    """alpha up to 10 (F(6,5)) runs through the unfused arrangement within 1e-3; f = 1 is less accurate than 1/2;
+    alpha_max above 10 is refused because the fp32 error of such tiles is above 1e-2."""
+    m = mnn()
+    layer = ConvLayer("k5", 1, 6, 24, 24, 8, 5, 5, 1, 2, 1, (-1.0, 1.0), BASE_SEED + 810)
+    x, w, b = draw(layer)
+    ref = oracle.conv2d(x, w, b, pad=2)
+    xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+    errs = {}
+    for n, f in ((6, 0.5), (5, 0.5), (4, 0.5), (4, 1.0)):
+        opt = m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=n, force_variant=0, alpha_max=10, point_scale_f=f)
+        with m.ConvPlan.for_layer(layer, options=opt) as plan:
+            y = plan.run(xd, wd, bd)
+            torch.cuda.synchronize()
+            errs[(n, f)] = oracle.error_ratio(y.cpu().numpy(), ref)
+    print(errs, flush=True)
+    assert errs[(4, 0.5)] <= 1e-3 and errs[(5, 0.5)] <= 1e-3 and errs[(6, 0.5)] <= 1e-3
+    assert errs[(4, 0.5)] < errs[(4, 1.0)]
+    with pytest.raises(m.MnnError) as e:
+        m.ConvPlan.for_layer(layer, options=m.Options(alpha_max=12))
+    assert e.value.code == -2
+
+
+def test_runs_are_bit_reproducible():
+    m = mnn()
+    layer = ConvLayer("repro", 2, 24, 20, 20, 40, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 811)
+    x, w, b = draw(layer)
+    xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+    for s, opt in all_forced(m, layer):
+        with m.ConvPlan.for_layer(layer, options=opt) as plan:
+            y1 = plan.run(xd, wd, bd).clone()
+            y2 = plan.run(xd, wd, bd)
+            torch.cuda.synchronize()
+            assert torch.equal(y1, y2), s.label(3)

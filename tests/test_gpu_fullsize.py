@@ -1,0 +1,75 @@
+"""Parity at the full sizes of the workloads, with the planner's own choice (the launch configuration
+bench.py times).  cfg3 and cfg4: the whole output against the oracle.  cfg5: the oracle at 4096 sampled
+output coordinates per layer (its full tensor would take minutes of float64 CPU time), drawn over all
+images, channels, edges and corners."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from conv_workloads import config_layers, draw
+
+pytestmark = pytest.mark.gpu
+
+
+def mnn():
+    import paper_2002_12418_amd as m
+    return m
+
+
+def tol_for(scheme, k, m):
+    return 1e-3 if (scheme.kind == m.SCHEME_WINOGRAD and scheme.tile_n + k - 1 > 6) else 1e-4
+
+
+@pytest.mark.parametrize("layer", config_layers(3) + config_layers(4), ids=lambda l: l.name)
+def test_cfg3_cfg4_full_tensor(layer):
+    m = mnn()
+    x, w, b = draw(layer)
+    ref = oracle.conv2d(x, w, b, stride=layer.stride, pad=layer.pad, dil=layer.dil)
+    xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+    with m.ConvPlan.for_layer(layer) as plan:
+        y = torch.full(plan.out_shape, float("nan"), device="cuda")
+        plan.run(xd, wd, bd, y)
+        torch.cuda.synchronize()
+        s = plan.scheme
+    got = y.cpu().numpy()
+    assert np.isfinite(got).all()
+    err = oracle.error_ratio(got, ref)
+    print(f"[full] {layer.name} {s.label(layer.kh)} err={err:.2e}", flush=True)
+    assert err <= tol_for(s, layer.kh, m)
+
+
+def sample_coords(shape, count, rng):
+    N, K, Ho, Wo = shape
+    c = np.stack([rng.integers(0, N, count), rng.integers(0, K, count), rng.integers(0, Ho, count), rng.integers(0, Wo, count)], axis=1)
+    # force corners, edges and the last tile row/column into the sample
+    k = 0
+    for n in (0, N - 1):
+        for kk in (0, K - 1):
+            for oy in (0, 1, Ho // 2, Ho - 2, Ho - 1):
+                for ox in (0, 1, Wo // 2, Wo - 2, Wo - 1):
+                    c[k] = (n, kk, oy, ox)
+                    k += 1
+    return c
+
+
+@pytest.mark.parametrize("layer", config_layers(5), ids=lambda l: l.name)
+def test_cfg5_sampled(layer):
+    m = mnn()
+    x, w, b = draw(layer)
+    xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+    rng = np.random.default_rng(layer.seed)
+    with m.ConvPlan.for_layer(layer) as plan:
+        y = torch.full(plan.out_shape, float("nan"), device="cuda")
+        plan.run(xd, wd, bd, y)
+        torch.cuda.synchronize()
+        s = plan.scheme
+        # properties that hold at any size: everything written, finite
+        assert bool(torch.isfinite(y).all())
+        coords = sample_coords(plan.out_shape, 4096, rng)
+    ref = oracle.conv2d_points(x, w, b, coords, stride=layer.stride, pad=layer.pad, dil=layer.dil)
+    got = y.cpu().numpy()[coords[:, 0], coords[:, 1], coords[:, 2], coords[:, 3]].astype(np.float64)
+    scale = float(torch.max(torch.abs(y)).item())
+    err = float(np.max(np.abs(got - ref))) / scale
+    print(f"[sampled] {layer.name} {s.label(layer.kh)} err={err:.2e}", flush=True)
+    assert err <= tol_for(s, layer.kh, m)

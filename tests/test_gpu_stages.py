@@ -1,0 +1,92 @@
+"""Each Winograd stage on its own against the float64 step-by-step oracle: U = G w G^T, V = B^T d B,
+M = U V (unfused arrangement), in the library's row layouts and in the blocked layouts of the fused
+arrangement."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import winograd
+from conv_workloads import ConvLayer, draw, BASE_SEED
+
+pytestmark = pytest.mark.gpu
+
+
+def mnn():
+    import paper_2002_12418_amd as m
+    return m
+
+
+CASES = [
+    # n, k, N, C, H, W, K, pad
+    (2, 3, 2, 5, 9, 7, 6, 1),
+    (4, 3, 3, 17, 14, 9, 33, 1),
+    (6, 3, 1, 8, 20, 20, 8, 1),
+    (4, 5, 1, 6, 12, 16, 7, 2),
+    (2, 7, 1, 4, 16, 16, 5, 3),
+    (3, 2, 2, 6, 9, 9, 4, 0),
+]
+
+
+def relerr(got, ref):
+    return float(np.max(np.abs(got.astype(np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_unfused_stage_buffers(case):
+    m = mnn()
+    n, k, N, C, H, W, K, pad = case
+    layer = ConvLayer("t", N, C, H, W, K, k, k, 1, pad, 1, (-1.0, 1.0), BASE_SEED + 500 + sum(case))
+    x, w, b = draw(layer)
+    yref, st = winograd.winograd_conv2d(x, w, b, n, pad=pad, return_stages=True)
+    a = n + k - 1
+    xd, wd, bd = (torch.from_numpy(t).cuda() for t in (x, w, b))
+    opt = m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=n, force_variant=m.WINO_UNFUSED)
+    with m.ConvPlan.for_layer(layer, options=opt) as plan:
+        info = plan.info
+        y = plan.run(xd, wd, bd)
+        torch.cuda.synchronize()
+        P, ldp, ldk = info["p"], info["ldp"], info["ldk"]
+        assert P == st["V"].shape[-1] and info["alpha"] == a
+        U = plan.buffer_to_numpy(m.BUF_U).reshape(a * a, C, ldk)
+        V = plan.buffer_to_numpy(m.BUF_V).reshape(a * a, C, ldp)
+        M = plan.buffer_to_numpy(m.BUF_M).reshape(a * a, K, ldp)
+    Uref = st["U"].reshape(a * a, K, C).transpose(0, 2, 1)            # library keeps U transposed: [xi][c][k]
+    assert relerr(U[:, :, :K], Uref) < 1e-5
+    assert np.all(U[:, :, K:] == 0)
+    assert relerr(V[:, :, :P], st["V"].reshape(a * a, C, P)) < 1e-5
+    assert np.all(V[:, :, P:] == 0)
+    assert relerr(M[:, :, :P], st["M"].reshape(a * a, K, P)) < 1e-4
+    assert oracle.error_ratio(y.cpu().numpy(), yref) < 1e-4
+
+
+@pytest.mark.parametrize("case", CASES[:4])
+def test_blocked_stage_buffers(case):
+    """Fused arrangement: Ub[b][c/4][a][k/16][c%4][k%16] and Vb[b][c/4][a][p/16][c%4][p%16], zero padding."""
+    m = mnn()
+    n, k, N, C, H, W, K, pad = case
+    layer = ConvLayer("t", N, C, H, W, K, k, k, 1, pad, 1, (-1.0, 1.0), BASE_SEED + 500 + sum(case))
+    x, w, b = draw(layer)
+    yref, st = winograd.winograd_conv2d(x, w, b, n, pad=pad, return_stages=True)
+    a = n + k - 1
+    xd, wd, bd = (torch.from_numpy(t).cuda() for t in (x, w, b))
+    opt = m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=n, force_variant=m.WINO_FUSED_OUT_32)
+    with m.ConvPlan.for_layer(layer, options=opt) as plan:
+        info = plan.info
+        y = plan.run(xd, wd, bd)
+        torch.cuda.synchronize()
+        P, kg, pg = info["p"], info["kg"], info["pg"]
+        U = plan.buffer_to_numpy(m.BUF_U)
+        V = plan.buffer_to_numpy(m.BUF_V)
+        assert plan.buffer(m.BUF_M)[0] == 0                           # the product tensor is never materialised
+    cch = U.size // (a * a * kg * 64)
+    assert cch * 4 >= C and V.size == a * cch * a * pg * 64
+    Ub = U.reshape(a, cch, a, kg, 4, 16)                              # [b][cc][a][kgroup][c%4][k%16]
+    Vb = V.reshape(a, cch, a, pg, 4, 16)
+    Ufull = Ub.transpose(2, 0, 1, 4, 3, 5).reshape(a, a, cch * 4, kg * 16)   # [a][b][c][k]
+    Vfull = Vb.transpose(2, 0, 1, 4, 3, 5).reshape(a, a, cch * 4, pg * 16)   # [a][b][c][p]
+    assert relerr(Ufull[:, :, :C, :K], st["U"].transpose(0, 1, 3, 2)) < 1e-5
+    assert relerr(Vfull[:, :, :C, :P], st["V"]) < 1e-5
+    for full, lim in ((Ufull, (C, K)), (Vfull, (C, P))):
+        assert np.all(full[:, :, lim[0]:, :] == 0) and np.all(full[:, :, :, lim[1]:] == 0)
+    assert oracle.error_ratio(y.cpu().numpy(), yref) < 1e-4
