@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the convolution hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {1..5}] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {1..5}] [--no-cpu-baseline] [--only-main]
 
 A step is one pass of the whole hot path over one batch of synthetic input: for
 every layer of the workload, input transform -> Winograd-domain GEMM -> output
-transform (or the 1x1 GEMM / direct kernel), with the scheme chosen by the
+transform (or the 1x1 GEMM / sliding-window kernel), with the scheme chosen by the
 pre-inference planner.  Inputs, weights and prepared weights are resident in HBM
-before the timed region.  One JSON line is printed.
+before the timed region.  The timed workload defaults to the largest family (the
+mixed-kernel stress at N = 16); the other families are run briefly afterwards and
+reported under "other_workloads".  One JSON line is printed.
 """
 from __future__ import annotations
 
@@ -47,27 +49,104 @@ def stage_work(layer, scheme, info, mnn):
 
 
 def cpu_baseline(layers):
-    """The float64 oracle, as it stands, timed on the host cores over the same workload."""
+    """The float64 oracle, as it stands, timed on the host cores over a bounded sample of the same workload:
+    whole images of every layer (images are independent), as many as fit about 1.5 s of wall time per layer,
+    i.e. roughly 10-30 s of CPU work on a 16-core host."""
     import oracle
     from conv_workloads import draw
     flops, secs = 0.0, 0.0
     names = []
-    budget_s = 40.0
+    cores = oracle.num_threads()
+    per_layer_s = 1.5
     for layer in layers:
-        sample = layer
-        # bound the sample: keep whole images, drop images until the estimate fits the budget
-        est = layer.direct_flops / 5e9
-        if est > budget_s / len(layers):
-            keep = max(1, int(layer.n * (budget_s / len(layers)) / est))
-            sample = layer.with_batch(keep)
-        x, w, b = draw(sample)
+        # a first single image gives the rate; then size the sample for the wall-time budget
+        one = layer.with_batch(1)
+        x, w, b = draw(one)
         t0 = time.perf_counter()
-        oracle.conv2d(x, w, b, stride=sample.stride, pad=sample.pad, dil=sample.dil)
+        oracle.conv2d(x, w, b, stride=one.stride, pad=one.pad, dil=one.dil)
+        t1 = time.perf_counter() - t0
+        keep = int(max(1, min(layer.n, per_layer_s / max(t1, 1e-4))))
+        sample = layer.with_batch(keep)
+        x, w, b = draw(sample)
+        # small layers finish in a fraction of the budget: repeat the pass so that the sample is not noise
+        reps = int(max(1, min(50, round(0.5 * per_layer_s / max(t1 * keep, 1e-4)))))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            oracle.conv2d(x, w, b, stride=sample.stride, pad=sample.pad, dil=sample.dil)
         secs += time.perf_counter() - t0
-        flops += sample.direct_flops
-        names.append(f"{sample.name}[N={sample.n}]")
-    return {"value": flops / secs / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "one float64 direct-convolution pass over " + ", ".join(names), "seconds": round(secs, 3)}
+        flops += sample.direct_flops * reps
+        names.append(f"{sample.name}[N={sample.n}]x{reps}")
+    return {"value": round(flops / secs / 1e9, 2), "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "float64 direct-convolution passes over " + ", ".join(names),
+            "seconds": round(secs, 3), "cpu_seconds": round(secs * cores, 1)}
+
+
+def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
+    """Plans every layer of workload `cfg`, times `steps` steps, and (detailed) times every kernel with HIP events."""
+    from conv_workloads import CONFIG_TITLES, config_layers, draw
+    layers = config_layers(cfg)
+    work = []
+    for layer in layers:
+        x, w, b = draw(layer)
+        xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+        layer_opt = opt
+        if opt is not None and opt.force_kind == mnn.SCHEME_WINOGRAD and (layer.stride != 1 or layer.kh == 1):
+            layer_opt = None
+        plan = mnn.ConvPlan.for_layer(layer, options=layer_opt, stream=stream)
+        y = torch.empty(plan.out_shape, dtype=torch.float32, device="cuda")
+        plan.run(xd, wd, bd, y, stream=stream)      # prepares the weights (filter transform) once
+        work.append((layer, plan, xd, wd, bd, y))
+    torch.cuda.synchronize()
+
+    def step():
+        for layer, plan, xd, wd, bd, y in work:
+            plan.run(xd, wd, bd, y, stream=stream)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    total_flops = float(sum(l.direct_flops for l in layers))
+    res = {"workload": CONFIG_TITLES[cfg], "layers_run": layers, "ms_per_step": elapsed / steps * 1e3,
+           "value": total_flops * steps / elapsed / 1e9}
+
+    # ---- per-kernel durations from HIP events on the launch stream (instrumented pass over the same work)
+    iters = max(5, min(steps, 50))
+    per_layer = []
+    stage_tot = {s: {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0} for s in STAGE_NAMES}
+    kernels = []
+    for layer, plan, xd, wd, bd, y in work:
+        ms = plan.run_timed(xd, wd, bd, y, iters=iters, stream=stream)
+        sch = plan.scheme
+        sw = stage_work(layer, sch, plan.info, mnn)
+        entry = {"layer": layer.name, "scheme": sch.label(layer.kh), "kernels": plan.describe(),
+                 "planner_ms": {c.label(layer.kh): round(c.est_ms, 4) for c in plan.candidates if c.est_ms >= 0},
+                 "stage_ms": {STAGE_NAMES[i]: round(ms[i], 5) for i in range(1, 4) if ms[i] > 0},
+                 "filter_ms_one_off": round(ms[0], 5)}
+        lay_ms = sum(ms[1:4])
+        entry["ms"] = round(lay_ms, 5)
+        entry["gflops_direct_count"] = round(layer.direct_flops / (lay_ms * 1e-3) / 1e9, 1) if lay_ms > 0 else None
+        for name, (fl, by) in sw.items():
+            i = STAGE_NAMES.index(name)
+            if ms[i] <= 0:
+                continue
+            st = stage_tot[name]
+            st["ms"] += ms[i]; st["flops"] += fl; st["bytes"] += by; st["launches"] += 1
+            entry.setdefault("stage_rate", {})[name] = {"TFLOP/s": round(fl / (ms[i] * 1e-3) / 1e12, 2),
+                                                        "GB/s": round(by / (ms[i] * 1e-3) / 1e9, 1)}
+            kernels.append({"layer": layer.name, "stage": name, "desc": plan.describe(), "ms": ms[i], "flops": fl, "bytes": by})
+        per_layer.append(entry)
+    res["per_layer"] = per_layer
+    res["stage_tot"] = stage_tot
+    res["kernels"] = kernels
+    for _, plan, *_rest in work:
+        plan.close()
+    return res
 
 
 def main():
@@ -75,9 +154,17 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5],
+                    help="workload family of the timed region (default 5: the largest single-GPU configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-main", action="store_true", help="skip the short runs of the other workload families")
     ap.add_argument("--force", type=str, default="", help="force a scheme: direct | gemm | F<n>  (default: planner)")
+    ap.add_argument("--plan-file", type=str, default="",
+                    help="pre-inference cache: loaded before planning if the file exists, written after planning. "
+                         "A second run with the same file launches no planner kernels (clean profiles)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, launch one plain 256 MiB device copy: a kernel of known traffic "
+                         "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of the same run can be scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); it has no multi-GPU path", file=sys.stderr)
@@ -85,13 +172,11 @@ def main():
 
     import torch
     import paper_2002_12418_amd as mnn
-    from conv_workloads import CONFIG_TITLES, config_layers, draw
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    layers = config_layers(args.config)
     opt = None
     if args.force:
         f = args.force.lower()
@@ -104,92 +189,64 @@ def main():
         else:
             raise SystemExit(f"unknown --force {args.force}")
 
+    if args.plan_file and os.path.exists(args.plan_file):
+        mnn.cache_load(args.plan_file)
     stream = torch.cuda.current_stream()
-    work = []
-    for layer in layers:
-        x, w, b = draw(layer)
-        xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
-        layer_opt = opt
-        if opt is not None and layer.stride != 1 and opt.force_kind == mnn.SCHEME_WINOGRAD:
-            layer_opt = mnn.Options(force_kind=mnn.SCHEME_DIRECT)
-        plan = mnn.ConvPlan.for_layer(layer, options=layer_opt, stream=stream)
-        y = torch.empty(plan.out_shape, dtype=torch.float32, device="cuda")
-        plan.run(xd, wd, bd, y, stream=stream)      # prepares the weights (filter transform) once
-        work.append((layer, plan, xd, wd, bd, y))
-    torch.cuda.synchronize()
+    main_res = run_workload(args.config, args.steps, args.warmup, opt, stream, mnn, torch)
+    layers = main_res["layers_run"]
 
-    def step():
-        for layer, plan, xd, wd, bd, y in work:
-            plan.run(xd, wd, bd, y, stream=stream)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    total_flops = float(sum(l.direct_flops for l in layers))
-    ms_per_step = elapsed / args.steps * 1e3
-    value = total_flops * args.steps / elapsed / 1e9
-
-    # ---- per-kernel durations from HIP events on the launch stream (instrumented pass, same work)
-    iters = max(5, min(args.steps, 50))
-    per_layer = []
-    stage_tot = {s: {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0} for s in STAGE_NAMES}
-    for layer, plan, xd, wd, bd, y in work:
-        ms = plan.run_timed(xd, wd, bd, y, iters=iters, stream=stream)
-        sch = plan.scheme
-        sw = stage_work(layer, sch, plan.info, mnn)
-        entry = {"layer": layer.name, "scheme": sch.label(layer.kh),
-                 "planner_ms": {c.label(layer.kh): round(c.est_ms, 4) for c in plan.candidates if c.est_ms >= 0},
-                 "stage_ms": {STAGE_NAMES[i]: round(ms[i], 5) for i in range(1, 4) if ms[i] > 0},
-                 "filter_ms_one_off": round(ms[0], 5)}
-        lay_ms = sum(ms[1:4])
-        entry["ms"] = round(lay_ms, 5)
-        entry["gflops_direct_count"] = round(layer.direct_flops / (lay_ms * 1e-3) / 1e9, 1) if lay_ms > 0 else None
-        for name, (fl, by) in sw.items():
-            i = STAGE_NAMES.index(name)
-            st = stage_tot[name]
-            st["ms"] += ms[i]; st["flops"] += fl; st["bytes"] += by; st["launches"] += 1
-            entry.setdefault("stage_rate", {})[name] = {
-                "TFLOP/s": round(fl / (ms[i] * 1e-3) / 1e12, 2) if ms[i] > 0 else None,
-                "GB/s": round(by / (ms[i] * 1e-3) / 1e9, 1) if ms[i] > 0 else None}
-        per_layer.append(entry)
-
-    dominant = max(STAGE_NAMES[1:], key=lambda s: stage_tot[s]["ms"])
-    st = stage_tot[dominant]
-    gemm_like = dominant == "gemm"
-    if gemm_like:
-        ach = st["flops"] / (st["ms"] * 1e-3) / 1e12
-        roofline = {"kernel": "gemm_f32_kernel (Winograd-domain / 1x1 / direct)", "bound": "mfma", "achieved": round(ach, 2),
+    # ---- roofline of the dominant kernel: the single launch of the step that takes longest
+    dom = max(main_res["kernels"], key=lambda k: k["ms"])
+    if dom["stage"] == "gemm":
+        ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        roofline = {"kernel": f"{dom['layer']}: {dom['desc']}", "bound": "mfma", "achieved": round(ach, 2),
                     "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / PEAK_FP32_MFMA_TFLOPS, 4),
                     "traffic": None}
     else:
-        ach = st["bytes"] / (st["ms"] * 1e-3) / 1e9
-        roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
-    roofline["avg_launch_ms"] = round(st["ms"] / max(1, st["launches"]), 5)
+        ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+        roofline = {"kernel": f"{dom['layer']}: {dom['stage']} of {dom['desc']}", "bound": "hbm", "achieved": round(ach, 1),
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+    roofline["avg_launch_ms"] = round(dom["ms"], 5)
+    roofline["algorithmic_flops_per_launch"] = dom["flops"]
+    roofline["algorithmic_bytes_per_launch"] = dom["bytes"]
     roofline["stages"] = {
-        s: {"ms_per_step": round(v["ms"], 5),
-            "TFLOP/s": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else None,
-            "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else None,
-            "frac_mfma": round(v["flops"] / (v["ms"] * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4) if v["ms"] > 0 else None,
-            "frac_hbm": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if v["ms"] > 0 else None}
-        for s, v in stage_tot.items() if v["launches"]}
+        s: {"ms_per_step": round(v["ms"], 5), "launches_per_step": v["launches"],
+            "TFLOP/s": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2),
+            "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1),
+            "frac_mfma": round(v["flops"] / (v["ms"] * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
+            "frac_hbm": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+        for s, v in main_res["stage_tot"].items() if v["launches"] and v["ms"] > 0}
 
     out = {
-        "metric": "conv GFLOP/s (direct-FLOP count)", "value": round(value, 1), "unit": "GFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "metric": "conv GFLOP/s (direct-FLOP count)", "value": round(main_res["value"], 1), "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(main_res["ms_per_step"], 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": CONFIG_TITLES[args.config], "layers": [l.name for l in layers],
+        "config": {"workload": main_res["workload"], "layers": [l.name for l in layers],
                    "batch": layers[0].n, "scheme": args.force or "planner"},
-        "ms_per_layer": {e["layer"]: e["ms"] for e in per_layer},
+        "ms_per_layer": {e["layer"]: e["ms"] for e in main_res["per_layer"]},
         "roofline": roofline,
-        "layers": per_layer,
+        "layers": main_res["per_layer"],
     }
+    if not args.only_main:
+        others = []
+        for cfg in (1, 2, 3, 4, 5):
+            if cfg == args.config:
+                continue
+            r = run_workload(cfg, max(5, min(args.steps, 20)), 2, opt, stream, mnn, torch)
+            others.append({"workload": r["workload"], "value": round(r["value"], 1), "unit": "GFLOP/s",
+                           "ms_per_step": round(r["ms_per_step"], 5),
+                           "layers": [{"layer": e["layer"], "scheme": e["scheme"], "ms": e["ms"], "stage_ms": e["stage_ms"],
+                                       "stage_rate": e.get("stage_rate", {})} for e in r["per_layer"]]})
+        out["other_workloads"] = others
+    if args.plan_file:
+        mnn.cache_save(args.plan_file)
+    if args.calibrate_copy:
+        n = 256 * 1024 * 1024 // 4
+        src = torch.rand(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = {"read": n * 4, "write": n * 4}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers)
     print(json.dumps(out))

@@ -147,6 +147,10 @@ int mnn_conv_plan_scheme(mnn_conv_plan_t plan, mnn_scheme* out);
  * most `cap` entries to out (may be NULL with cap 0) and the total to *count.  Host. */
 int mnn_conv_plan_candidates(mnn_conv_plan_t plan, mnn_scheme* out, int32_t cap, int32_t* count);
 
+/* Human-readable description of what the plan launches, e.g. "F(4,3) unfused gemm=128x64x16_w2x2".
+ * Writes at most cap bytes including the terminating NUL.  Host. */
+int mnn_conv_plan_describe(mnn_conv_plan_t plan, char* buf, size_t cap);
+
 /* Geometry of the plan.  Host. */
 int mnn_conv_plan_info(mnn_conv_plan_t plan, mnn_plan_info* out);
 
@@ -243,6 +247,13 @@ const char* mnn_gemm_variant_name(int32_t variant);
 /* Process-wide cache of planner choices keyed by device, shape, geometry and options. */
 int mnn_conv_cache_size(void);
 void mnn_conv_cache_clear(void);
+
+/* Pre-inference results outlive the process: mnn_conv_cache_save writes every cached choice (scheme per
+ * layer shape, GEMM tile configuration per matrix shape) to a text file, mnn_conv_cache_load merges such a
+ * file into the cache, so that a later mnn_conv_plan for a known shape launches no timing kernels.
+ * path: host, NUL-terminated.  Entries are keyed by the HIP device ordinal they were measured on. */
+int mnn_conv_cache_save(const char* path);
+int mnn_conv_cache_load(const char* path);
 
 const char* mnn_last_error(void);
 int mnn_version(void);

@@ -74,6 +74,7 @@ def _load() -> ctypes.CDLL:
     L.mnn_conv_plan_scheme.argtypes = [vp, POINTER(_Scheme)]
     L.mnn_conv_plan_candidates.argtypes = [vp, POINTER(_Scheme), c_int32, POINTER(c_int32)]
     L.mnn_conv_plan_info.argtypes = [vp, POINTER(_Info)]
+    L.mnn_conv_plan_describe.argtypes = [vp, ctypes.c_char_p, c_size_t]
     L.mnn_conv_workspace_bytes.argtypes = [vp]
     L.mnn_conv_workspace_bytes.restype = c_size_t
     L.mnn_conv_run.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -97,6 +98,8 @@ def _load() -> ctypes.CDLL:
     L.mnn_conv_cache_size.argtypes = []
     L.mnn_conv_cache_clear.argtypes = []
     L.mnn_conv_cache_clear.restype = None
+    L.mnn_conv_cache_save.argtypes = [c_char_p]
+    L.mnn_conv_cache_load.argtypes = [c_char_p]
     L.mnn_last_error.restype = c_char_p
     L.mnn_version.argtypes = []
     return L
@@ -241,6 +244,14 @@ def cache_clear() -> None:
     lib.mnn_conv_cache_clear()
 
 
+def cache_save(path: str) -> None:
+    _check(lib.mnn_conv_cache_save(os.fsencode(path)))
+
+
+def cache_load(path: str) -> None:
+    _check(lib.mnn_conv_cache_load(os.fsencode(path)))
+
+
 def _stream_handle(stream) -> int:
     import torch
     if stream is None:
@@ -282,6 +293,11 @@ class ConvPlan:
         buf = (_Scheme * 64)()
         _check(lib.mnn_conv_plan_candidates(self._h, buf, 64, byref(cnt)))
         return [Scheme._from(buf[i]) for i in range(min(64, cnt.value))]
+
+    def describe(self) -> str:
+        buf = ctypes.create_string_buffer(256)
+        _check(lib.mnn_conv_plan_describe(self._h, buf, 256))
+        return buf.value.decode()
 
     @property
     def workspace_bytes(self) -> int:

@@ -703,6 +703,25 @@ int mnn_conv_plan_candidates(mnn_conv_plan_t plan, mnn_scheme* out, int32_t cap,
     return MNN_OK;
 }
 
+int mnn_conv_plan_describe(mnn_conv_plan_t plan, char* buf, size_t cap)
+{
+    if (!plan || !buf || cap == 0) return fail(MNN_E_INVALID_ARG, "bad argument");
+    const Impl& im = plan->impl;
+    const char* gv = gemm_f32_variant_name(im.gemm_variant);
+    switch (im.scheme.kind) {
+        case MNN_SCHEME_WINOGRAD:
+            if (im.scheme.variant == MNN_WINO_UNFUSED)
+                std::snprintf(buf, cap, "F(%d,%d) unfused gemm=%s", im.wg.n, im.wg.k, gv ? gv : "?");
+            else
+                std::snprintf(buf, cap, "F(%d,%d) fused-output %s", im.wg.n, im.wg.k,
+                              im.scheme.variant == MNN_WINO_FUSED_OUT_32 ? "32x32" : "64x64");
+            break;
+        case MNN_SCHEME_GEMM1X1: std::snprintf(buf, cap, "gemm1x1 gemm=%s", gv ? gv : "?"); break;
+        default: std::snprintf(buf, cap, "sliding-window implicit gemm=%s", gv ? gv : "?"); break;
+    }
+    return MNN_OK;
+}
+
 int mnn_conv_plan_info(mnn_conv_plan_t plan, mnn_plan_info* out)
 {
     if (!plan || !out) return fail(MNN_E_INVALID_ARG, "NULL argument");
@@ -914,6 +933,88 @@ void mnn_conv_cache_clear(void)
 {
     std::lock_guard<std::mutex> lk(g_cache_mu);
     g_cache.clear();
+}
+
+int mnn_conv_cache_save(const char* path)
+{
+    if (!path) return fail(MNN_E_INVALID_ARG, "path is NULL");
+    FILE* f = std::fopen(path, "w");
+    if (!f) return fail(MNN_E_INVALID_ARG, "cannot open %s for writing", path);
+    std::fprintf(f, "mnnconv-plan-cache 1\n");
+    {
+        std::lock_guard<std::mutex> lk(g_cache_mu);
+        for (const auto& kv : g_cache) {
+            const std::vector<int>& v = std::get<1>(kv.first);
+            std::fprintf(f, "S %d %zu", std::get<0>(kv.first), v.size());
+            for (int x : v) std::fprintf(f, " %d", x);
+            std::fprintf(f, " %.9g | %d %d %d %d %.6g\n", (double)std::get<2>(kv.first), kv.second.kind, kv.second.tile_n,
+                         kv.second.prec, kv.second.variant, (double)kv.second.est_ms);
+        }
+    }
+    {
+        std::lock_guard<std::mutex> lk(g_gemm_mu);
+        for (const auto& kv : g_gemm_choice) {
+            const std::vector<long long>& v = std::get<1>(kv.first);
+            std::fprintf(f, "G %d %zu", std::get<0>(kv.first), v.size());
+            for (long long x : v) std::fprintf(f, " %lld", x);
+            std::fprintf(f, " | %d\n", kv.second);
+        }
+    }
+    const bool ok = std::fclose(f) == 0;
+    return ok ? MNN_OK : fail(MNN_E_INVALID_ARG, "error writing %s", path);
+}
+
+int mnn_conv_cache_load(const char* path)
+{
+    if (!path) return fail(MNN_E_INVALID_ARG, "path is NULL");
+    FILE* f = std::fopen(path, "r");
+    if (!f) return fail(MNN_E_INVALID_ARG, "cannot open %s", path);
+    int version = 0;
+    int rc = MNN_OK;
+    try {
+        if (std::fscanf(f, "mnnconv-plan-cache %d", &version) != 1 || version != 1) {
+            rc = fail(MNN_E_INVALID_ARG, "%s is not a plan cache of this library", path);
+        } else {
+            char tag[4];
+            while (!rc && std::fscanf(f, "%3s", tag) == 1) {
+                int dev = 0;
+                size_t n = 0;
+                if (std::fscanf(f, "%d %zu", &dev, &n) != 2 || n > 64) { rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path); break; }
+                if (tag[0] == 'S') {
+                    std::vector<int> v(n);
+                    for (size_t i = 0; i < n && !rc; ++i)
+                        if (std::fscanf(f, "%d", &v[i]) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
+                    double fscale = 0, est = 0;
+                    mnn_scheme sc{};
+                    if (!rc && std::fscanf(f, "%lf | %d %d %d %d %lf", &fscale, &sc.kind, &sc.tile_n, &sc.prec, &sc.variant, &est) != 6)
+                        rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
+                    if (!rc) {
+                        sc.est_ms = (float)est;
+                        std::lock_guard<std::mutex> lk(g_cache_mu);
+                        g_cache[CacheKey(dev, v, (float)fscale)] = sc;
+                    }
+                } else if (tag[0] == 'G') {
+                    std::vector<long long> v(n);
+                    for (size_t i = 0; i < n && !rc; ++i)
+                        if (std::fscanf(f, "%lld", &v[i]) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
+                    int variant = 0;
+                    if (!rc && std::fscanf(f, " | %d", &variant) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
+                    if (!rc && (variant < 0 || variant >= gemm_f32_variant_count()))
+                        rc = fail(MNN_E_INVALID_ARG, "unknown GEMM configuration %d in %s", variant, path);
+                    if (!rc) {
+                        std::lock_guard<std::mutex> lk(g_gemm_mu);
+                        g_gemm_choice[GemmKey(dev, v)] = variant;
+                    }
+                } else {
+                    rc = fail(MNN_E_INVALID_ARG, "unknown entry type in %s", path);
+                }
+            }
+        }
+    } catch (...) {
+        rc = fail(MNN_E_OOM, "host allocation failed");
+    }
+    std::fclose(f);
+    return rc;
 }
 
 const char* mnn_last_error(void) { return g_err.c_str(); }

@@ -173,3 +173,23 @@ def test_product_path_does_not_import_the_oracle():
             if f.endswith((".py", ".c")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "paper_2002_12418_amd" not in text and "mnn_conv" not in text, f
+
+
+def test_cache_file_round_trip_rejects_garbage(mnn, tmp_path):
+    good = tmp_path / "plans.txt"
+    mnn.cache_clear()
+    mnn.cache_save(str(good))
+    assert good.read_text().startswith("mnnconv-plan-cache 1")
+    mnn.cache_load(str(good))
+    assert mnn.cache_size() == 0
+    # a hand-written entry: device 0, cfg1 layer with the default options, F(4,3) unfused
+    good.write_text("mnnconv-plan-cache 1\nS 0 15 1 16 32 32 16 3 3 1 1 1 1 1 1 8 0 0.5 | 2 4 0 0 0.01\n")
+    mnn.cache_load(str(good))
+    assert mnn.cache_size() == 1
+    mnn.cache_clear()
+    bad = tmp_path / "bad.txt"
+    bad.write_text("something else\n")
+    with pytest.raises(mnn.MnnError):
+        mnn.cache_load(str(bad))
+    with pytest.raises(mnn.MnnError):
+        mnn.cache_load(str(tmp_path / "missing.txt"))
