@@ -258,7 +258,6 @@ struct Impl {
     Layer L{};
     WinogradMatrices mats;
     WinoGeom wg{};
-    DirectGeom dg{};
     float* U = nullptr; size_t U_bytes = 0;
     float* V = nullptr; size_t V_bytes = 0;
     float* M = nullptr; size_t M_bytes = 0;
@@ -353,10 +352,6 @@ struct Impl {
             U_bytes = (size_t)sh.c_in * sh.kh * sh.kw * ldk * sizeof(float);
             int rcd = alloc_zero(&U, U_bytes, "hipMalloc Wt");
             if (rcd) return rcd;
-            dg.N = sh.n; dg.C = sh.c_in; dg.H = sh.h; dg.W = sh.w; dg.K = sh.c_out; dg.kh = sh.kh; dg.kw = sh.kw;
-            dg.Ho = L.Ho; dg.Wo = L.Wo;
-            dg.stride_h = L.g.stride_h; dg.stride_w = L.g.stride_w; dg.pad_h = L.g.pad_h; dg.pad_w = L.g.pad_w;
-            dg.dil_h = L.g.dil_h; dg.dil_w = L.g.dil_w;
             return MNN_OK;
         }
         return fail(MNN_E_INVALID_ARG, "unknown scheme kind %d", s.kind);

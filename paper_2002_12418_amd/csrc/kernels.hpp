@@ -86,12 +86,4 @@ const char* gemm_f32_variant_name(int variant);
 // Wt[r][k] = w[k][r], r < R = C*kh*kw, row length ldk (zero padded)
 hipError_t launch_weight_transpose(const float* w, float* Wt, int K, int R, int ldk, hipStream_t s);
 
-struct DirectGeom {
-    int N, C, H, W, K, kh, kw, Ho, Wo;
-    int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
-};
-// Sliding-window convolution straight from the definition.
-hipError_t launch_direct_conv(const DirectGeom& g, const float* x, const float* w, const float* bias,
-                              float* y, hipStream_t s);
-
 }  // namespace mnnconv
