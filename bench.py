@@ -159,6 +159,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-main", action="store_true", help="skip the short runs of the other workload families")
     ap.add_argument("--force", type=str, default="", help="force a scheme: direct | gemm | F<n>  (default: planner)")
+    ap.add_argument("--allow-bf16", action="store_true",
+                    help="let the planner of the timed region also use the bf16 matrix cores (bf16x3 split operands); "
+                         "without it the timed region is fp32 end to end and the bf16 result is reported separately")
     ap.add_argument("--plan-file", type=str, default="",
                     help="pre-inference cache: loaded before planning if the file exists, written after planning. "
                          "A second run with the same file launches no planner kernels (clean profiles)")
@@ -192,6 +195,8 @@ def main():
     if args.plan_file and os.path.exists(args.plan_file):
         mnn.cache_load(args.plan_file)
     stream = torch.cuda.current_stream()
+    if args.allow_bf16 and opt is None:
+        opt = mnn.Options(allow_bf16=1)
     main_res = run_workload(args.config, args.steps, args.warmup, opt, stream, mnn, torch)
     layers = main_res["layers_run"]
 
@@ -220,13 +225,21 @@ def main():
     out = {
         "metric": "conv GFLOP/s (direct-FLOP count)", "value": round(main_res["value"], 1), "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(main_res["ms_per_step"], 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (bf16x3 matrix-core operands allowed)" if args.allow_bf16 else "f32", "data": "synthetic",
         "config": {"workload": main_res["workload"], "layers": [l.name for l in layers],
                    "batch": layers[0].n, "scheme": args.force or "planner"},
         "ms_per_layer": {e["layer"]: e["ms"] for e in main_res["per_layer"]},
         "roofline": roofline,
         "layers": main_res["per_layer"],
     }
+    if not args.only_main and not args.allow_bf16 and not args.force:
+        # the same workload with the bf16 matrix cores allowed (split operands, fp32 accumulation): reported, not `value`
+        r = run_workload(args.config, max(5, min(args.steps, 20)), 2, mnn.Options(allow_bf16=1), stream, mnn, torch)
+        out["with_bf16_matrix_cores"] = {
+            "value": round(r["value"], 1), "unit": "GFLOP/s", "ms_per_step": round(r["ms_per_step"], 5),
+            "layers": [{"layer": e["layer"], "scheme": e["scheme"], "kernels": e["kernels"], "ms": e["ms"],
+                        "stage_ms": e["stage_ms"]} for e in r["per_layer"]]}
     if not args.only_main:
         others = []
         for cfg in (1, 2, 3, 4, 5):

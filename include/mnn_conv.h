@@ -58,7 +58,9 @@ typedef enum {
 /* Operand precision of the matrix-multiplication stage (accumulation is always fp32). */
 typedef enum {
     MNN_GEMM_FP32 = 0,        /* fp32 operands, v_mfma_f32_32x32x2_f32                    */
-    MNN_GEMM_BF16 = 1         /* bf16 operands (RNE), bf16 MFMA                           */
+    MNN_GEMM_BF16 = 1,        /* operands rounded to bf16 (RNE), v_mfma_f32_32x32x16_bf16 */
+    MNN_GEMM_BF16X3 = 2       /* each operand split into bf16 hi + lo, product = hi*hi + hi*lo + lo*hi on
+                                 the bf16 matrix cores: about 16 mantissa bits, fp32-grade results    */
 } mnn_gemm_prec;
 
 typedef struct {
@@ -84,7 +86,9 @@ typedef struct {
     int32_t force_tile_n;     /* with force_kind == WINOGRAD: the n to use (0 = analytic) */
     int32_t force_prec;       /* mnn_gemm_prec used for forced schemes                    */
     int32_t force_variant;    /* MNN_WINO_* used for a forced Winograd scheme; -1 = time the variants */
-    int32_t allow_bf16;       /* 1: AUTO may also time bf16 candidates                    */
+    int32_t allow_bf16;       /* 1: AUTO may also time bf16-matrix-core candidates: BF16X3 for every scheme with a
+                                 separate GEMM stage, plain BF16 for the 1x1 and sliding-window schemes only
+                                 (plain bf16 Winograd operands miss the 2e-2 bound for most tiles)   */
     int32_t alpha_max;        /* largest n + k - 1 the planner may generate (default 8, max 10:
                                  beyond that the fp32 error of the transforms exceeds 1e-3)          */
     float   point_scale_f;    /* f of the Winograd generator (default 0.5)                */
@@ -233,16 +237,17 @@ int mnn_conv_select(const mnn_scheme* cands, int32_t count, int32_t k, int32_t* 
  * B element (r, col) lives at  B + b*strideB_batch + (col / L)*strideB_img + r*strideB_row + col % L,
  * D element (m, col) at        D + b*strideD_batch + (col / L)*strideD_img + m*strideD_row + col % L
  * (L = run of columns that is contiguous in memory; strides in elements).
- * variant 0 picks the tile configuration from the shape; 1..mnn_gemm_variant_count()-1 force one.
+ * prec is a mnn_gemm_prec.  variant 0 picks the tile configuration from the shape;
+ * 1..mnn_gemm_variant_count(prec)-1 force one.
  */
 typedef struct {
-    int32_t M, ncols, R, batch, lda, L, variant;
+    int32_t M, ncols, R, batch, lda, L, variant, prec;
     int64_t strideA_batch, strideB_batch, strideB_img, strideB_row, strideD_batch, strideD_img, strideD_row;
 } mnn_gemm_desc;
 int mnn_gemm_f32(const mnn_gemm_desc* desc, const float* At, const float* B, const float* bias, float* D,
                  void* stream);
-int mnn_gemm_variant_count(void);
-const char* mnn_gemm_variant_name(int32_t variant);
+int mnn_gemm_variant_count(int32_t prec);
+const char* mnn_gemm_variant_name(int32_t prec, int32_t variant);
 
 /* Process-wide cache of planner choices keyed by device, shape, geometry and options. */
 int mnn_conv_cache_size(void);

@@ -18,7 +18,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libmnnconv.so")
 
 SCHEME_AUTO, SCHEME_DIRECT, SCHEME_WINOGRAD, SCHEME_GEMM1X1 = 0, 1, 2, 3
-GEMM_FP32, GEMM_BF16 = 0, 1
+GEMM_FP32, GEMM_BF16, GEMM_BF16X3 = 0, 1, 2
 STAGE_FILTER, STAGE_INPUT, STAGE_GEMM, STAGE_OUTPUT, STAGE_COUNT = 0, 1, 2, 3, 4
 BUF_U, BUF_V, BUF_M = 0, 1, 2
 WINO_UNFUSED, WINO_FUSED_OUT_32, WINO_FUSED_OUT_64 = 0, 1, 2
@@ -50,7 +50,7 @@ class _Options(ctypes.Structure):
 
 
 class _GemmDesc(ctypes.Structure):
-    _fields_ = [(n, c_int32) for n in ("M", "ncols", "R", "batch", "lda", "L", "variant")] + \
+    _fields_ = [(n, c_int32) for n in ("M", "ncols", "R", "batch", "lda", "L", "variant", "prec")] + \
                [(n, ctypes.c_int64) for n in ("strideA_batch", "strideB_batch", "strideB_img", "strideB_row",
                                               "strideD_batch", "strideD_img", "strideD_row")]
 
@@ -92,8 +92,8 @@ def _load() -> ctypes.CDLL:
                                      POINTER(c_int32)]
     L.mnn_conv_select.argtypes = [POINTER(_Scheme), c_int32, c_int32, POINTER(c_int32)]
     L.mnn_gemm_f32.argtypes = [POINTER(_GemmDesc), vp, vp, vp, vp, vp]
-    L.mnn_gemm_variant_count.argtypes = []
-    L.mnn_gemm_variant_name.argtypes = [c_int32]
+    L.mnn_gemm_variant_count.argtypes = [c_int32]
+    L.mnn_gemm_variant_name.argtypes = [c_int32, c_int32]
     L.mnn_gemm_variant_name.restype = c_char_p
     L.mnn_conv_cache_size.argtypes = []
     L.mnn_conv_cache_clear.argtypes = []
@@ -130,7 +130,7 @@ class Scheme:
     est_ms: float = -1.0
 
     def label(self, k: Optional[int] = None) -> str:
-        p = "" if self.prec == GEMM_FP32 else "/bf16"
+        p = {GEMM_FP32: "", GEMM_BF16: "/bf16", GEMM_BF16X3: "/bf16x3"}.get(self.prec, f"/p{self.prec}")
         if self.kind == SCHEME_WINOGRAD:
             v = {WINO_UNFUSED: "", WINO_FUSED_OUT_32: "+fo32", WINO_FUSED_OUT_64: "+fo64"}.get(self.variant, f"+v{self.variant}")
             return f"F({self.tile_n},{k if k is not None else 'k'}){v}{p}"
@@ -219,16 +219,16 @@ def select_scheme(cands: Sequence[Scheme], k: int) -> int:
     return int(out.value)
 
 
-def gemm_variants() -> List[str]:
-    return [lib.mnn_gemm_variant_name(i).decode() for i in range(lib.mnn_gemm_variant_count())]
+def gemm_variants(prec: int = GEMM_FP32) -> List[str]:
+    return [lib.mnn_gemm_variant_name(prec, i).decode() for i in range(lib.mnn_gemm_variant_count(prec))]
 
 
-def gemm_f32(At, B, D, bias=None, *, M, ncols, R, batch=1, lda=None, L=None, variant=0,
+def gemm_f32(At, B, D, bias=None, *, M, ncols, R, batch=1, lda=None, L=None, variant=0, prec=GEMM_FP32,
              strideA_batch=0, strideB_batch=0, strideB_img=0, strideB_row=None,
              strideD_batch=0, strideD_img=0, strideD_row=None, stream=None):
     """mnn_gemm_f32 on device tensors (only their data_ptr() is used)."""
     L = ncols if L is None else L
-    d = _GemmDesc(M, ncols, R, batch, M if lda is None else lda, L, variant, strideA_batch, strideB_batch,
+    d = _GemmDesc(M, ncols, R, batch, M if lda is None else lda, L, variant, prec, strideA_batch, strideB_batch,
                   strideB_img, L if strideB_row is None else strideB_row, strideD_batch, strideD_img,
                   L if strideD_row is None else strideD_row)
     _check(lib.mnn_gemm_f32(byref(d), At.data_ptr(), B.data_ptr(), bias.data_ptr() if bias is not None else None,

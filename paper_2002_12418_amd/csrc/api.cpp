@@ -98,7 +98,7 @@ int validate_options(const mnn_conv_options* in, mnn_conv_options* o)
     if (o->plan_warmup < 0 || o->plan_iters <= 0) return fail(MNN_E_INVALID_ARG, "plan_warmup >= 0 and plan_iters > 0 required");
     if (o->force_kind < MNN_SCHEME_AUTO || o->force_kind > MNN_SCHEME_GEMM1X1)
         return fail(MNN_E_INVALID_ARG, "unknown force_kind %d", o->force_kind);
-    if (o->force_prec != MNN_GEMM_FP32 && o->force_prec != MNN_GEMM_BF16)
+    if (o->force_prec < MNN_GEMM_FP32 || o->force_prec > MNN_GEMM_BF16X3)
         return fail(MNN_E_INVALID_ARG, "unknown force_prec %d", o->force_prec);
     if (o->force_variant < -1 || o->force_variant >= MNN_WINO_VARIANTS)
         return fail(MNN_E_INVALID_ARG, "unknown force_variant %d", o->force_variant);
@@ -144,14 +144,20 @@ void push_wino_variants(std::vector<mnn_scheme>* out, int n, int k, int prec)
 std::vector<mnn_scheme> enumerate(const Layer& L, const mnn_conv_options& o)
 {
     std::vector<mnn_scheme> out;
-    if (is_pointwise(L)) {
-        out.push_back(make_scheme(MNN_SCHEME_GEMM1X1, 0, MNN_GEMM_FP32));
-        return out;
+    const int base = is_pointwise(L) ? MNN_SCHEME_GEMM1X1 : MNN_SCHEME_DIRECT;
+    out.push_back(make_scheme(base, 0, MNN_GEMM_FP32));
+    if (o.allow_bf16) {
+        out.push_back(make_scheme(base, 0, MNN_GEMM_BF16X3));
+        out.push_back(make_scheme(base, 0, MNN_GEMM_BF16));
     }
-    out.push_back(make_scheme(MNN_SCHEME_DIRECT, 0, MNN_GEMM_FP32));
+    if (is_pointwise(L)) return out;
     if (winograd_admissible(L)) {
         const int k = L.s.kh;
-        for (int n = 2; n + k - 1 <= o.alpha_max; ++n) push_wino_variants(&out, n, k, MNN_GEMM_FP32);
+        for (int n = 2; n + k - 1 <= o.alpha_max; ++n) {
+            push_wino_variants(&out, n, k, MNN_GEMM_FP32);
+            if (o.allow_bf16 && winograd_kernels_available(n, k))
+                out.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, MNN_GEMM_BF16X3, MNN_WINO_UNFUSED));
+        }
     }
     return out;
 }
@@ -206,7 +212,7 @@ GemmKey gemm_key(int device, const GemmProblem& p)
     std::vector<long long> v = {p.M, p.Ncols, p.R, p.batch, p.lda, p.L, p.strideA_batch, p.strideB_batch, p.strideB_img,
                                 p.strideB_row, p.strideD_batch, p.strideD_img, p.strideD_row, p.bias ? 1 : 0,
                                 p.gather, p.cv_C, p.cv_H, p.cv_W, p.cv_kh, p.cv_kw, p.cv_sh, p.cv_sw, p.cv_ph, p.cv_pw,
-                                p.cv_dh, p.cv_dw, p.cv_Wo};
+                                p.cv_dh, p.cv_dw, p.cv_Wo, p.prec};
     return GemmKey(device, v);
 }
 
@@ -229,7 +235,7 @@ int tune_gemm(GemmProblem p, hipStream_t s, int* variant_out)
     float best_ms = -1.f;
     const int iters = 4;
     int rc = MNN_OK;
-    for (int v = 1; v < gemm_f32_variant_count() && !rc; ++v) {
+    for (int v = 1; v < gemm_variant_count(p.prec) && !rc; ++v) {
         p.variant = v;
         e = launch_gemm_f32(p, s);                                   // warm-up, also tells whether v applies
         if (e == hipErrorInvalidValue) { (void)hipGetLastError(); continue; }
@@ -296,7 +302,8 @@ struct Impl {
         scheme = s;
         const mnn_conv_shape& sh = L.s;
         ldk = round_up(sh.c_out, 4);
-        if (s.prec != MNN_GEMM_FP32) return fail(MNN_E_UNSUPPORTED, "bf16 GEMM is not built into this library yet");
+        if (s.prec != MNN_GEMM_FP32 && s.kind == MNN_SCHEME_WINOGRAD && s.variant != MNN_WINO_UNFUSED)
+            return fail(MNN_E_UNSUPPORTED, "the fused Winograd kernels multiply in fp32 only");
         if (s.kind == MNN_SCHEME_WINOGRAD) {
             if (!winograd_admissible(L)) return fail(MNN_E_UNSUPPORTED, "Winograd needs a square kernel >= 2, stride 1, dilation 1");
             const int n = s.tile_n, k = sh.kh;
@@ -367,6 +374,7 @@ struct Impl {
         p.strideB_batch = (long long)wg.C * wg.ldp; p.strideB_img = 0; p.strideB_row = wg.ldp;
         p.strideD_batch = (long long)wg.K * wg.ldp; p.strideD_img = 0; p.strideD_row = wg.ldp;
         p.variant = gemm_variant;
+        p.prec = scheme.prec;
         return p;
     }
 
@@ -382,6 +390,7 @@ struct Impl {
         p.strideB_batch = 0; p.strideB_img = (long long)sh.c_in * HW; p.strideB_row = HW;
         p.strideD_batch = 0; p.strideD_img = (long long)sh.c_out * HW; p.strideD_row = HW;
         p.variant = gemm_variant;
+        p.prec = scheme.prec;
         return p;
     }
 
@@ -395,6 +404,7 @@ struct Impl {
         p.lda = ldk; p.L = HoWo;
         p.strideD_img = (long long)sh.c_out * HoWo; p.strideD_row = HoWo;
         p.variant = gemm_variant;
+        p.prec = scheme.prec;
         p.gather = 1;
         p.cv_C = sh.c_in; p.cv_H = sh.h; p.cv_W = sh.w; p.cv_kh = sh.kh; p.cv_kw = sh.kw;
         p.cv_sh = L.g.stride_h; p.cv_sw = L.g.stride_w; p.cv_ph = L.g.pad_h; p.cv_pw = L.g.pad_w;
@@ -702,7 +712,7 @@ int mnn_conv_plan_describe(mnn_conv_plan_t plan, char* buf, size_t cap)
 {
     if (!plan || !buf || cap == 0) return fail(MNN_E_INVALID_ARG, "bad argument");
     const Impl& im = plan->impl;
-    const char* gv = gemm_f32_variant_name(im.gemm_variant);
+    const char* gv = gemm_variant_name(im.scheme.prec, im.gemm_variant);
     switch (im.scheme.kind) {
         case MNN_SCHEME_WINOGRAD:
             if (im.scheme.variant == MNN_WINO_UNFUSED)
@@ -905,6 +915,8 @@ int mnn_gemm_f32(const mnn_gemm_desc* d, const float* At, const float* B, const 
     p.At = At; p.B = B; p.D = D; p.bias = bias;
     p.M = d->M; p.Ncols = d->ncols; p.R = d->R; p.batch = d->batch; p.lda = d->lda; p.L = d->L;
     p.variant = d->variant;
+    p.prec = d->prec;
+    if (p.prec < MNN_GEMM_FP32 || p.prec > MNN_GEMM_BF16X3) return fail(MNN_E_INVALID_ARG, "unknown precision %d", p.prec);
     p.strideA_batch = d->strideA_batch;
     p.strideB_batch = d->strideB_batch; p.strideB_img = d->strideB_img; p.strideB_row = d->strideB_row;
     p.strideD_batch = d->strideD_batch; p.strideD_img = d->strideD_img; p.strideD_row = d->strideD_row;
@@ -914,9 +926,15 @@ int mnn_gemm_f32(const mnn_gemm_desc* d, const float* At, const float* B, const 
     return MNN_OK;
 }
 
-int mnn_gemm_variant_count(void) { return gemm_f32_variant_count(); }
+int mnn_gemm_variant_count(int32_t prec)
+{
+    return (prec < MNN_GEMM_FP32 || prec > MNN_GEMM_BF16X3) ? 0 : gemm_variant_count(prec);
+}
 
-const char* mnn_gemm_variant_name(int32_t variant) { return gemm_f32_variant_name(variant); }
+const char* mnn_gemm_variant_name(int32_t prec, int32_t variant)
+{
+    return (prec < MNN_GEMM_FP32 || prec > MNN_GEMM_BF16X3) ? nullptr : gemm_variant_name(prec, variant);
+}
 
 int mnn_conv_cache_size(void)
 {
@@ -994,7 +1012,8 @@ int mnn_conv_cache_load(const char* path)
                         if (std::fscanf(f, "%lld", &v[i]) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
                     int variant = 0;
                     if (!rc && std::fscanf(f, " | %d", &variant) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
-                    if (!rc && (variant < 0 || variant >= gemm_f32_variant_count()))
+                    const int vprec = v.empty() ? 0 : (int)v.back();
+                    if (!rc && (vprec < 0 || vprec > MNN_GEMM_BF16X3 || variant < 0 || variant >= gemm_variant_count(vprec)))
                         rc = fail(MNN_E_INVALID_ARG, "unknown GEMM configuration %d in %s", variant, path);
                     if (!rc) {
                         std::lock_guard<std::mutex> lk(g_gemm_mu);

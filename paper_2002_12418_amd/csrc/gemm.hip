@@ -270,6 +270,7 @@ const char* gemm_f32_variant_name(int v)
 
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s)
 {
+    if (p.prec != 0) return launch_gemm_bf16(p, s);
     if (!p.At || !p.B || !p.D) return hipErrorInvalidValue;
     if (p.M <= 0 || p.Ncols <= 0 || p.R <= 0 || p.batch <= 0 || p.L <= 0) return hipErrorInvalidValue;
     if (p.lda < p.M || (p.lda & 3) || !aligned16(p.At) || (p.strideA_batch & 3)) return hipErrorInvalidValue;

@@ -156,8 +156,21 @@ def test_plan_argument_validation(mnn):
 
 
 def test_gemm_variant_table(mnn):
-    names = mnn.gemm_variants()
-    assert names[0] == "auto" and len(names) == len(set(names)) and len(names) > 4
+    for prec in (mnn.GEMM_FP32, mnn.GEMM_BF16, mnn.GEMM_BF16X3):
+        names = mnn.gemm_variants(prec)
+        assert names[0] == "auto" and len(names) == len(set(names)) and len(names) > 4
+    assert mnn.gemm_variants(7) == []
+
+
+def test_enumeration_with_bf16_allowed(mnn):
+    c = mnn.enumerate_schemes(1, 64, 56, 56, 64, 3, 3, pad=1, options=mnn.Options(allow_bf16=1))
+    x3 = [s for s in c if s.prec == mnn.GEMM_BF16X3]
+    plain = [s for s in c if s.prec == mnn.GEMM_BF16]
+    # split-operand variant for the sliding window and every F(n,3); plain bf16 only for the sliding window
+    assert sorted(s.tile_n for s in x3) == [0, 2, 3, 4, 5, 6] and all(s.variant == 0 for s in x3)
+    assert [(s.kind, s.tile_n) for s in plain] == [(mnn.SCHEME_DIRECT, 0)]
+    c = mnn.enumerate_schemes(16, 32, 112, 112, 64, 1, 1, options=mnn.Options(allow_bf16=1))
+    assert [(s.kind, s.prec) for s in c] == [(mnn.SCHEME_GEMM1X1, 0), (mnn.SCHEME_GEMM1X1, 2), (mnn.SCHEME_GEMM1X1, 1)]
 
 
 def test_product_path_does_not_import_the_oracle():

@@ -85,3 +85,35 @@ def test_planner_choice_is_correct_and_listed(layer):
     assert err <= tol_for(scheme, layer.kh)
     if layer.stride != 1:
         assert scheme.kind == m.SCHEME_DIRECT
+
+
+BF16_TOL = 2e-2        # bound for the bf16-matrix-core variants
+BF16X3_TOL = 5e-4      # what the split-operand variant is held to here (measured <= 3.1e-4 at alpha = 8)
+
+
+@pytest.mark.parametrize("layer", small_parity_layers() + config_layers(1) + config_layers(2), ids=lambda l: l.name)
+def test_bf16_matrix_core_schemes(layer):
+    """Every scheme the planner may use with allow_bf16: bf16x3 for all GEMM-stage schemes, plain bf16 for the
+    1x1 and sliding-window schemes."""
+    m = mnn()
+    seen = 0
+    for s in m.enumerate_schemes(layer.n, layer.c_in, layer.h, layer.w, layer.c_out, layer.kh, layer.kw,
+                                 stride=layer.stride, pad=layer.pad, dil=layer.dil, options=m.Options(allow_bf16=1)):
+        if s.prec == m.GEMM_FP32:
+            continue
+        print(f"[case] {layer.name} {s.label(layer.kh)}", flush=True)
+        opt = m.Options(force_kind=s.kind, force_tile_n=s.tile_n, force_prec=s.prec, force_variant=s.variant)
+        err, scheme = run_and_compare(layer, opt)
+        assert scheme.prec == s.prec
+        assert err <= (BF16X3_TOL if s.prec == m.GEMM_BF16X3 else BF16_TOL), (layer.name, s.label(layer.kh), err)
+        seen += 1
+    assert seen >= 2
+
+
+def test_planner_with_bf16_allowed_stays_within_the_bf16_bound():
+    m = mnn()
+    m.cache_clear()
+    for layer in config_layers(2)[:5]:
+        err, scheme = run_and_compare(layer, m.Options(allow_bf16=1))
+        assert err <= (tol_for(scheme, layer.kh) if scheme.prec == m.GEMM_FP32 else BF16_TOL)
+    m.cache_clear()

@@ -92,9 +92,9 @@ def test_inadmissible_forced_schemes_are_refused():
     with pytest.raises(m.MnnError) as e:
         m.ConvPlan.for_layer(config_layers(1)[0], options=m.Options(force_kind=m.SCHEME_GEMM1X1))
     assert e.value.code == -2
-    with pytest.raises(m.MnnError) as e:
+    with pytest.raises(m.MnnError) as e:     # the fused arrangement multiplies in fp32 only
         m.ConvPlan.for_layer(config_layers(1)[0], options=m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=2,
-                                                                     force_prec=m.GEMM_BF16, force_variant=0))
+                                                                     force_prec=m.GEMM_BF16X3, force_variant=1))
     assert e.value.code == -2
 
 
