@@ -205,7 +205,8 @@ int select_scheme(const mnn_scheme* c, int count, int k)
 // itself it is chosen by measurement at pre-inference time and remembered per shape.
 using GemmKey = std::tuple<int, std::vector<long long>>;
 std::mutex g_gemm_mu;
-std::map<GemmKey, int> g_gemm_choice;
+struct GemmChoice { int variant; int splitk; };
+std::map<GemmKey, GemmChoice> g_gemm_choice;
 
 GemmKey gemm_key(int device, const GemmProblem& p)
 {
@@ -216,8 +217,25 @@ GemmKey gemm_key(int device, const GemmProblem& p)
     return GemmKey(device, v);
 }
 
-// Times every usable configuration on the given (valid, writable) buffers; returns the fastest id.
-int tune_gemm(GemmProblem p, hipStream_t s, int* variant_out)
+// Times one configuration (warm-up + `iters` launches between two events); *ms < 0 when it does not apply.
+int time_gemm(const GemmProblem& p, hipStream_t s, hipEvent_t e0, hipEvent_t e1, int iters, float* ms)
+{
+    *ms = -1.f;
+    hipError_t e = launch_gemm_f32(p, s);
+    if (e == hipErrorInvalidValue) { (void)hipGetLastError(); return MNN_OK; }
+    if (e != hipSuccess) return fail_hip(e, "gemm tuning launch");
+    if ((e = hipEventRecord(e0, s)) != hipSuccess) return fail_hip(e, "hipEventRecord");
+    for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_gemm_f32(p, s);
+    if (e != hipSuccess) return fail_hip(e, "gemm tuning launch");
+    if ((e = hipEventRecord(e1, s)) != hipSuccess) return fail_hip(e, "hipEventRecord");
+    if ((e = hipEventSynchronize(e1)) != hipSuccess) return fail_hip(e, "hipEventSynchronize");
+    if ((e = hipEventElapsedTime(ms, e0, e1)) != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
+    return MNN_OK;
+}
+
+// Times every usable tile configuration -- and, where the tiles do not fill the chip, every useful
+// split of the reduction -- on the given (valid, writable) buffers; returns the fastest.
+int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
 {
     int dev = 0;
     (void)hipGetDevice(&dev);
@@ -225,34 +243,52 @@ int tune_gemm(GemmProblem p, hipStream_t s, int* variant_out)
     {
         std::lock_guard<std::mutex> lk(g_gemm_mu);
         auto it = g_gemm_choice.find(key);
-        if (it != g_gemm_choice.end()) { *variant_out = it->second; return MNN_OK; }
+        if (it != g_gemm_choice.end()) { *out = it->second; return MNN_OK; }
     }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     hipError_t e;
     if ((e = hipEventCreate(&e0)) != hipSuccess) return fail_hip(e, "hipEventCreate");
     if ((e = hipEventCreate(&e1)) != hipSuccess) { (void)hipEventDestroy(e0); return fail_hip(e, "hipEventCreate"); }
-    int best = 0;
+    GemmChoice best{0, 1};
     float best_ms = -1.f;
     const int iters = 4;
     int rc = MNN_OK;
     for (int v = 1; v < gemm_variant_count(p.prec) && !rc; ++v) {
         p.variant = v;
-        e = launch_gemm_f32(p, s);                                   // warm-up, also tells whether v applies
-        if (e == hipErrorInvalidValue) { (void)hipGetLastError(); continue; }
-        if (e != hipSuccess) { rc = fail_hip(e, "gemm tuning launch"); break; }
-        if ((e = hipEventRecord(e0, s)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
-        for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_gemm_f32(p, s);
-        if (e != hipSuccess) { rc = fail_hip(e, "gemm tuning launch"); break; }
-        if ((e = hipEventRecord(e1, s)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
-        if ((e = hipEventSynchronize(e1)) != hipSuccess) { rc = fail_hip(e, "hipEventSynchronize"); break; }
-        float ms = 0.f;
-        if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) { rc = fail_hip(e, "hipEventElapsedTime"); break; }
-        if (best_ms < 0.f || ms < best_ms) { best_ms = ms; best = v; }
+        p.splitk = 1; p.splitk_partial = nullptr; p.splitk_counters = nullptr;
+        float ms = -1.f;
+        if ((rc = time_gemm(p, s, e0, e1, iters, &ms))) break;
+        if (ms >= 0.f && (best_ms < 0.f || ms < best_ms)) { best_ms = ms; best = GemmChoice{v, 1}; }
+        int bm = 0, bn = 0, bk = 0;
+        if (ms < 0.f || !gemm_variant_tile(p.prec, v, &bm, &bn, &bk)) continue;
+        const long long tiles = (long long)((p.M + bm - 1) / bm) * ((p.Ncols + bn - 1) / bn) * p.batch;
+        const int chunks = (p.R + bk - 1) / bk;
+        for (int sk = 2; sk <= 32 && !rc; sk *= 2) {
+            if (tiles >= 384 || tiles * sk > 1024 || sk > chunks) break;
+            if ((long long)(sk - 1) * ((chunks + sk - 1) / sk) >= chunks) continue;     // an empty slice
+            long long pf = 0, cn = 0;
+            gemm_splitk_workspace(p, bm, bn, sk, &pf, &cn);
+            float* part = nullptr;
+            unsigned* cnt = nullptr;
+            if ((e = hipMalloc((void**)&part, (size_t)pf * sizeof(float))) != hipSuccess ||
+                (e = hipMalloc((void**)&cnt, (size_t)cn * sizeof(unsigned))) != hipSuccess ||
+                (e = hipMemset(cnt, 0, (size_t)cn * sizeof(unsigned))) != hipSuccess) {
+                if (part) (void)hipFree(part);
+                if (cnt) (void)hipFree(cnt);
+                rc = fail_hip(e, "hipMalloc split-K scratch");
+                break;
+            }
+            p.splitk = sk; p.splitk_partial = part; p.splitk_counters = cnt;
+            rc = time_gemm(p, s, e0, e1, iters, &ms);
+            (void)hipFree(part);
+            (void)hipFree(cnt);
+            if (!rc && ms >= 0.f && ms < best_ms) { best_ms = ms; best = GemmChoice{v, sk}; }
+        }
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (rc) return rc;
-    *variant_out = best;
+    *out = best;
     std::lock_guard<std::mutex> lk(g_gemm_mu);
     g_gemm_choice[key] = best;
     return MNN_OK;
@@ -269,6 +305,9 @@ struct Impl {
     float* M = nullptr; size_t M_bytes = 0;
     int ldk = 0;
     int gemm_variant = 0;      // tile configuration of the GEMM stage (0 = shape heuristic)
+    int gemm_splitk = 1;       // workgroups per tile along the reduction
+    float* sk_partial = nullptr; size_t sk_partial_bytes = 0;
+    unsigned* sk_counters = nullptr; size_t sk_counters_bytes = 0;
 
     ~Impl() { release(); }
     Impl() = default;
@@ -280,8 +319,12 @@ struct Impl {
         if (U) (void)hipFree(U);
         if (V) (void)hipFree(V);
         if (M) (void)hipFree(M);
+        if (sk_partial) (void)hipFree(sk_partial);
+        if (sk_counters) (void)hipFree(sk_counters);
         U = V = M = nullptr;
-        U_bytes = V_bytes = M_bytes = 0;
+        sk_partial = nullptr;
+        sk_counters = nullptr;
+        U_bytes = V_bytes = M_bytes = sk_partial_bytes = sk_counters_bytes = 0;
     }
 
     int alloc_zero(float** p, size_t bytes, const char* what)
@@ -373,9 +416,17 @@ struct Impl {
         p.strideA_batch = (long long)wg.C * ldk;
         p.strideB_batch = (long long)wg.C * wg.ldp; p.strideB_img = 0; p.strideB_row = wg.ldp;
         p.strideD_batch = (long long)wg.K * wg.ldp; p.strideD_img = 0; p.strideD_row = wg.ldp;
-        p.variant = gemm_variant;
-        p.prec = scheme.prec;
+        set_gemm_choice(&p);
         return p;
+    }
+
+    void set_gemm_choice(GemmProblem* p) const
+    {
+        p->variant = gemm_variant;
+        p->prec = scheme.prec;
+        p->splitk = gemm_splitk;
+        p->splitk_partial = sk_partial;
+        p->splitk_counters = sk_counters;
     }
 
     GemmProblem pointwise_gemm_problem(const float* x, const float* b, float* y) const
@@ -389,8 +440,7 @@ struct Impl {
         p.strideA_batch = 0;
         p.strideB_batch = 0; p.strideB_img = (long long)sh.c_in * HW; p.strideB_row = HW;
         p.strideD_batch = 0; p.strideD_img = (long long)sh.c_out * HW; p.strideD_row = HW;
-        p.variant = gemm_variant;
-        p.prec = scheme.prec;
+        set_gemm_choice(&p);
         return p;
     }
 
@@ -403,8 +453,7 @@ struct Impl {
         p.M = sh.c_out; p.Ncols = sh.n * HoWo; p.R = sh.c_in * sh.kh * sh.kw; p.batch = 1;
         p.lda = ldk; p.L = HoWo;
         p.strideD_img = (long long)sh.c_out * HoWo; p.strideD_row = HoWo;
-        p.variant = gemm_variant;
-        p.prec = scheme.prec;
+        set_gemm_choice(&p);
         p.gather = 1;
         p.cv_C = sh.c_in; p.cv_H = sh.h; p.cv_W = sh.w; p.cv_kh = sh.kh; p.cv_kw = sh.kw;
         p.cv_sh = L.g.stride_h; p.cv_sw = L.g.stride_w; p.cv_ph = L.g.pad_h; p.cv_pw = L.g.pad_w;
@@ -414,10 +463,33 @@ struct Impl {
 
     // Picks the GEMM tile configuration by timing (pre-inference).  The 1x1 scheme multiplies the
     // caller's tensors, so it is tuned on scratch tensors of the layer's size.
+    int adopt(const GemmProblem& p, const GemmChoice& c)
+    {
+        gemm_variant = c.variant;
+        gemm_splitk = c.splitk > 1 ? c.splitk : 1;
+        if (gemm_splitk == 1) return MNN_OK;
+        int bm = 0, bn = 0, bk = 0;
+        if (!gemm_variant_tile(p.prec, gemm_variant, &bm, &bn, &bk)) { gemm_splitk = 1; return MNN_OK; }
+        long long pf = 0, cn = 0;
+        gemm_splitk_workspace(p, bm, bn, gemm_splitk, &pf, &cn);
+        sk_partial_bytes = (size_t)pf * sizeof(float);
+        sk_counters_bytes = (size_t)cn * sizeof(unsigned);
+        int rc = alloc_zero(&sk_partial, sk_partial_bytes, "hipMalloc split-K partials");
+        if (rc) return rc;
+        float* c32 = nullptr;
+        rc = alloc_zero(&c32, sk_counters_bytes, "hipMalloc split-K counters");
+        sk_counters = reinterpret_cast<unsigned*>(c32);
+        return rc;
+    }
+
     int tune(hipStream_t s)
     {
-        if (scheme.kind == MNN_SCHEME_WINOGRAD && scheme.variant == MNN_WINO_UNFUSED)
-            return tune_gemm(wino_gemm_problem(), s, &gemm_variant);
+        GemmChoice c{0, 1};
+        if (scheme.kind == MNN_SCHEME_WINOGRAD && scheme.variant == MNN_WINO_UNFUSED) {
+            const GemmProblem p = wino_gemm_problem();
+            int rc = tune_gemm(p, s, &c);
+            return rc ? rc : adopt(p, c);
+        }
         if (scheme.kind == MNN_SCHEME_GEMM1X1 || scheme.kind == MNN_SCHEME_DIRECT) {
             const mnn_conv_shape& sh = L.s;
             const size_t xb = (size_t)sh.n * sh.c_in * sh.h * sh.w * sizeof(float);
@@ -430,13 +502,12 @@ struct Impl {
                 rc = fail_hip(e, "hipMalloc tuning scratch");
             if (!rc && ((e = hipMemset(tx, 0, xb)) != hipSuccess || (e = hipMemset(tb, 0, (size_t)sh.c_out * sizeof(float))) != hipSuccess))
                 rc = fail_hip(e, "hipMemset tuning scratch");
-            if (!rc)
-                rc = tune_gemm(scheme.kind == MNN_SCHEME_DIRECT ? direct_gemm_problem(tx, tb, ty)
-                                                                : pointwise_gemm_problem(tx, tb, ty), s, &gemm_variant);
+            GemmProblem p = scheme.kind == MNN_SCHEME_DIRECT ? direct_gemm_problem(tx, tb, ty) : pointwise_gemm_problem(tx, tb, ty);
+            if (!rc) rc = tune_gemm(p, s, &c);
             if (tx) (void)hipFree(tx);
             if (ty) (void)hipFree(ty);
             if (tb) (void)hipFree(tb);
-            return rc;
+            return rc ? rc : adopt(p, c);
         }
         return MNN_OK;
     }
@@ -486,7 +557,7 @@ struct Impl {
         return MNN_OK;
     }
 
-    size_t bytes() const { return U_bytes + V_bytes + M_bytes; }
+    size_t bytes() const { return U_bytes + V_bytes + M_bytes + sk_partial_bytes + sk_counters_bytes; }
 };
 
 // ------------------------------------------------------------------ choice cache
@@ -712,7 +783,9 @@ int mnn_conv_plan_describe(mnn_conv_plan_t plan, char* buf, size_t cap)
 {
     if (!plan || !buf || cap == 0) return fail(MNN_E_INVALID_ARG, "bad argument");
     const Impl& im = plan->impl;
-    const char* gv = gemm_variant_name(im.scheme.prec, im.gemm_variant);
+    std::string gvs = gemm_variant_name(im.scheme.prec, im.gemm_variant) ? gemm_variant_name(im.scheme.prec, im.gemm_variant) : "?";
+    if (im.gemm_splitk > 1) gvs += " splitk=" + std::to_string(im.gemm_splitk);
+    const char* gv = gvs.c_str();
     switch (im.scheme.kind) {
         case MNN_SCHEME_WINOGRAD:
             if (im.scheme.variant == MNN_WINO_UNFUSED)
@@ -970,7 +1043,7 @@ int mnn_conv_cache_save(const char* path)
             const std::vector<long long>& v = std::get<1>(kv.first);
             std::fprintf(f, "G %d %zu", std::get<0>(kv.first), v.size());
             for (long long x : v) std::fprintf(f, " %lld", x);
-            std::fprintf(f, " | %d\n", kv.second);
+            std::fprintf(f, " | %d %d\n", kv.second.variant, kv.second.splitk);
         }
     }
     const bool ok = std::fclose(f) == 0;
@@ -1010,14 +1083,15 @@ int mnn_conv_cache_load(const char* path)
                     std::vector<long long> v(n);
                     for (size_t i = 0; i < n && !rc; ++i)
                         if (std::fscanf(f, "%lld", &v[i]) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
-                    int variant = 0;
-                    if (!rc && std::fscanf(f, " | %d", &variant) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
+                    int variant = 0, splitk = 1;
+                    if (!rc && std::fscanf(f, " | %d %d", &variant, &splitk) != 2) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
+                    if (!rc && (splitk < 1 || splitk > 32)) rc = fail(MNN_E_INVALID_ARG, "bad split in %s", path);
                     const int vprec = v.empty() ? 0 : (int)v.back();
                     if (!rc && (vprec < 0 || vprec > MNN_GEMM_BF16X3 || variant < 0 || variant >= gemm_variant_count(vprec)))
                         rc = fail(MNN_E_INVALID_ARG, "unknown GEMM configuration %d in %s", variant, path);
                     if (!rc) {
                         std::lock_guard<std::mutex> lk(g_gemm_mu);
-                        g_gemm_choice[GemmKey(dev, v)] = variant;
+                        g_gemm_choice[GemmKey(dev, v)] = GemmChoice{variant, splitk};
                     }
                 } else {
                     rc = fail(MNN_E_INVALID_ARG, "unknown entry type in %s", path);

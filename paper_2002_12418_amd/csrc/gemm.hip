@@ -23,6 +23,7 @@
 // then hit the same L2.
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
+#include "gemm_splitk.hpp"
 
 namespace mnnconv {
 namespace {
@@ -61,7 +62,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     const int wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
 
-    const int logical = xcd_remap((int)blockIdx.x, total);
+    const int splitk = p.splitk > 1 ? p.splitk : 1;
+    const int wg = xcd_remap((int)blockIdx.x, total * splitk);
+    const int logical = wg / splitk;          // slices of one tile are neighbours: same XCD, same L2
+    const int split = wg % splitk;
     const int tm = logical % tilesM;
     const int t2 = logical / tilesM;
     const int tn = t2 % tilesN;
@@ -164,8 +168,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nchunks = (p.R + BK - 1) / BK;
-    load_global(0);
+    const int all_chunks = (p.R + BK - 1) / BK;
+    const int per_split = (all_chunks + splitk - 1) / splitk;
+    const int ch0 = split * per_split;
+    const int nchunks = (all_chunks - ch0 < per_split ? all_chunks - ch0 : per_split);   // launcher guarantees >= 1
+    load_global(ch0 * BK);
     store_lds(0);
     __syncthreads();
 
@@ -176,7 +183,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
 
     for (int ch = 0; ch < nchunks; ++ch) {
         const int buf = ch & 1;
-        if (ch + 1 < nchunks) load_global((ch + 1) * BK);
+        if (ch + 1 < nchunks) load_global((ch0 + ch + 1) * BK);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             float av[TM], bv[TN];
@@ -194,6 +201,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
         __syncthreads();
     }
 
+    if (splitk > 1) {
+        if (!splitk_combine<TM, TN, NT>(acc, p.splitk_partial, p.splitk_counters, logical, split, splitk, tid)) return;
+    }
     // ---- epilogue: lane holds column lcol of each tile, rows 8*(r/4) + 4*(lane/32) + r%4
     float* __restrict__ Db = p.D + (long long)b * p.strideD_batch;
 #pragma unroll
@@ -224,14 +234,22 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
     const int tilesN = (p.Ncols + BN - 1) / BN;
     const long long total = (long long)tilesM * tilesN * p.batch;
     if (total <= 0 || total >= (1ll << 31)) return hipErrorInvalidValue;
+    const int splitk = p.splitk > 1 ? p.splitk : 1;
+    if (splitk > 1) {
+        // every slice needs at least one chunk, and the scratch buffers must be there
+        const int all_chunks = (p.R + BK - 1) / BK;
+        const int per_split = (all_chunks + splitk - 1) / splitk;
+        if ((long long)(splitk - 1) * per_split >= all_chunks || !p.splitk_partial || !p.splitk_counters || total * splitk >= (1ll << 31))
+            return hipErrorInvalidValue;
+    }
     if (p.gather)
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2>), dim3((unsigned)total), dim3(WM * WN * 64),
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
                            0, s, p, tilesM, tilesN, (int)total);
     else if (vec)
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1>), dim3((unsigned)total), dim3(WM * WN * 64),
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
                            0, s, p, tilesM, tilesN, (int)total);
     else
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0>), dim3((unsigned)total), dim3(WM * WN * 64),
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
                            0, s, p, tilesM, tilesN, (int)total);
     return hipGetLastError();
 }
@@ -241,20 +259,20 @@ inline bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 
 }  // namespace
 
 namespace {
-struct Variant { const char* name; hipError_t (*fn)(const GemmProblem&, bool, hipStream_t); int bm, bn; };
+struct Variant { const char* name; hipError_t (*fn)(const GemmProblem&, bool, hipStream_t); int bm, bn, bk; };
 const Variant kVariants[] = {
-    {"auto", nullptr, 0, 0},
-    {"128x128x16_w2x2", launch_cfg<128, 128, 16, 2, 2>, 128, 128},
-    {"64x128x16_w1x4", launch_cfg<64, 128, 16, 1, 4>, 64, 128},
-    {"128x128x32_w2x2", launch_cfg<128, 128, 32, 2, 2>, 128, 128},
-    {"128x64x16_w2x2", launch_cfg<128, 64, 16, 2, 2>, 128, 64},
-    {"128x64x32_w2x2", launch_cfg<128, 64, 32, 2, 2>, 128, 64},
-    {"256x128x16_w4x2", launch_cfg<256, 128, 16, 4, 2>, 256, 128},
-    {"64x64x16_w2x2", launch_cfg<64, 64, 16, 2, 2>, 64, 64},
-    {"64x64x32_w2x2", launch_cfg<64, 64, 32, 2, 2>, 64, 64},
-    {"128x128x16_w4x2", launch_cfg<128, 128, 16, 4, 2>, 128, 128},
-    {"64x128x32_w1x4", launch_cfg<64, 128, 32, 1, 4>, 64, 128},
-    {"64x256x16_w1x4", launch_cfg<64, 256, 16, 1, 4>, 64, 256},
+    {"auto", nullptr, 0, 0, 0},
+    {"128x128x16_w2x2", launch_cfg<128, 128, 16, 2, 2>, 128, 128, 16},
+    {"64x128x16_w1x4", launch_cfg<64, 128, 16, 1, 4>, 64, 128, 16},
+    {"128x128x32_w2x2", launch_cfg<128, 128, 32, 2, 2>, 128, 128, 32},
+    {"128x64x16_w2x2", launch_cfg<128, 64, 16, 2, 2>, 128, 64, 16},
+    {"128x64x32_w2x2", launch_cfg<128, 64, 32, 2, 2>, 128, 64, 32},
+    {"256x128x16_w4x2", launch_cfg<256, 128, 16, 4, 2>, 256, 128, 16},
+    {"64x64x16_w2x2", launch_cfg<64, 64, 16, 2, 2>, 64, 64, 16},
+    {"64x64x32_w2x2", launch_cfg<64, 64, 32, 2, 2>, 64, 64, 32},
+    {"128x128x16_w4x2", launch_cfg<128, 128, 16, 4, 2>, 128, 128, 16},
+    {"64x128x32_w1x4", launch_cfg<64, 128, 32, 1, 4>, 64, 128, 32},
+    {"64x256x16_w1x4", launch_cfg<64, 256, 16, 1, 4>, 64, 256, 16},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 }  // namespace
@@ -266,6 +284,25 @@ const char* gemm_f32_variant_name(int v)
 {
     if (v >= 0 && v < kNumVariants) return kVariants[v].name;
     return gemm_f32_async_variant_name(v - kNumVariants);
+}
+
+bool gemm_f32_variant_tile(int v, int* bm, int* bn, int* bk)
+{
+    if (v < 1 || v >= kNumVariants) return false;       // the persistent kernels do not split K
+    *bm = kVariants[v].bm; *bn = kVariants[v].bn; *bk = kVariants[v].bk;
+    return true;
+}
+
+bool gemm_variant_tile(int prec, int variant, int* bm, int* bn, int* bk)
+{
+    return prec == 0 ? gemm_f32_variant_tile(variant, bm, bn, bk) : gemm_bf16_variant_tile(variant, bm, bn, bk);
+}
+
+void gemm_splitk_workspace(const GemmProblem& p, int bm, int bn, int splitk, long long* partial_floats, long long* counters)
+{
+    const long long tiles = (long long)((p.M + bm - 1) / bm) * ((p.Ncols + bn - 1) / bn) * p.batch;
+    *counters = tiles;
+    *partial_floats = tiles * splitk * bm * bn;
 }
 
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s)
@@ -281,7 +318,10 @@ hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s)
             return hipErrorInvalidValue;
         if (p.variant >= kNumVariants) return hipErrorInvalidValue;   // the direct-to-LDS kernels cannot gather
     }
-    if (p.variant >= kNumVariants) return launch_gemm_f32_async(p, p.variant - kNumVariants, s);
+    if (p.variant >= kNumVariants) {
+        if (p.splitk > 1) return hipErrorInvalidValue;
+        return launch_gemm_f32_async(p, p.variant - kNumVariants, s);
+    }
     const bool vec = aligned16(p.B) && (p.L % 4 == 0) && (p.Ncols % 4 == 0) && (p.strideB_batch % 4 == 0) &&
                      (p.strideB_img % 4 == 0) && (p.strideB_row % 4 == 0);
     int v = p.variant;

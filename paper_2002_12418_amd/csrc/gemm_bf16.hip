@@ -21,6 +21,7 @@
 // 8*(l/32) .. +7, column l%32) is four dwords, row pairs 4*(l/32) .. +3.
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
+#include "gemm_splitk.hpp"
 
 namespace mnnconv {
 namespace {
@@ -79,7 +80,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmProblem p, 
     const int wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
 
-    const int logical = xcd_remap((int)blockIdx.x, total);
+    const int splitk = p.splitk > 1 ? p.splitk : 1;
+    const int wg = xcd_remap((int)blockIdx.x, total * splitk);
+    const int logical = wg / splitk;          // slices of one tile are neighbours: same XCD, same L2
+    const int split = wg % splitk;
     const int tm = logical % tilesM;
     const int t2 = logical / tilesM;
     const int tn = t2 % tilesN;
@@ -204,8 +208,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmProblem p, 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nchunks = (p.R + BK - 1) / BK;
-    load_global(0);
+    const int all_chunks = (p.R + BK - 1) / BK;
+    const int per_split = (all_chunks + splitk - 1) / splitk;
+    const int ch0 = split * per_split;
+    const int nchunks = (all_chunks - ch0 < per_split ? all_chunks - ch0 : per_split);   // launcher guarantees >= 1
+    load_global(ch0 * BK);
     store_lds(0);
     __syncthreads();
 
@@ -223,7 +230,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmProblem p, 
 
     for (int ch = 0; ch < nchunks; ++ch) {
         const int buf = ch & 1;
-        if (ch + 1 < nchunks) load_global((ch + 1) * BK);
+        if (ch + 1 < nchunks) load_global((ch0 + ch + 1) * BK);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 ah[TM], al[TM], bh[TN], bl[TN];
@@ -253,6 +260,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmProblem p, 
         __syncthreads();
     }
 
+    if (splitk > 1) {
+        if (!splitk_combine<TM, TN, NT>(acc, p.splitk_partial, p.splitk_counters, logical, split, splitk, tid)) return;
+    }
     float* __restrict__ Db = p.D + (long long)b * p.strideD_batch;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -282,7 +292,15 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
     const int tilesN = (p.Ncols + BN - 1) / BN;
     const long long total = (long long)tilesM * tilesN * p.batch;
     if (total <= 0 || total >= (1ll << 31)) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)total), block(WM * WN * 64);
+    const int splitk = p.splitk > 1 ? p.splitk : 1;
+    if (splitk > 1) {
+        // every slice needs at least one chunk, and the scratch buffers must be there
+        const int all_chunks = (p.R + BK - 1) / BK;
+        const int per_split = (all_chunks + splitk - 1) / splitk;
+        if ((long long)(splitk - 1) * per_split >= all_chunks || !p.splitk_partial || !p.splitk_counters || total * splitk >= (1ll << 31))
+            return hipErrorInvalidValue;
+    }
+    const dim3 grid((unsigned)(total * splitk)), block(WM * WN * 64);
     const bool split = p.prec == 2;
 #define MNN_LAUNCH(MODE_)                                                                                         \
     do {                                                                                                          \
@@ -302,20 +320,27 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
 
 inline bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
-struct Variant { const char* name; hipError_t (*fn)(const GemmProblem&, bool, hipStream_t); };
+struct Variant { const char* name; hipError_t (*fn)(const GemmProblem&, bool, hipStream_t); int bm, bn, bk; };
 const Variant kVariants[] = {
-    {"auto", nullptr},
-    {"bf16_128x128x32_w2x2", launch_cfg<128, 128, 32, 2, 2>},
-    {"bf16_64x128x32_w1x4", launch_cfg<64, 128, 32, 1, 4>},
-    {"bf16_128x64x32_w2x2", launch_cfg<128, 64, 32, 2, 2>},
-    {"bf16_64x64x32_w2x2", launch_cfg<64, 64, 32, 2, 2>},
-    {"bf16_128x128x16_w2x2", launch_cfg<128, 128, 16, 2, 2>},
-    {"bf16_64x64x64_w2x2", launch_cfg<64, 64, 64, 2, 2>},
-    {"bf16_256x128x32_w4x2", launch_cfg<256, 128, 32, 4, 2>},
+    {"auto", nullptr, 0, 0, 0},
+    {"bf16_128x128x32_w2x2", launch_cfg<128, 128, 32, 2, 2>, 128, 128, 32},
+    {"bf16_64x128x32_w1x4", launch_cfg<64, 128, 32, 1, 4>, 64, 128, 32},
+    {"bf16_128x64x32_w2x2", launch_cfg<128, 64, 32, 2, 2>, 128, 64, 32},
+    {"bf16_64x64x32_w2x2", launch_cfg<64, 64, 32, 2, 2>, 64, 64, 32},
+    {"bf16_128x128x16_w2x2", launch_cfg<128, 128, 16, 2, 2>, 128, 128, 16},
+    {"bf16_64x64x64_w2x2", launch_cfg<64, 64, 64, 2, 2>, 64, 64, 64},
+    {"bf16_256x128x32_w4x2", launch_cfg<256, 128, 32, 4, 2>, 256, 128, 32},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
 }  // namespace
+
+bool gemm_bf16_variant_tile(int v, int* bm, int* bn, int* bk)
+{
+    if (v < 1 || v >= kNumVariants) return false;
+    *bm = kVariants[v].bm; *bn = kVariants[v].bn; *bk = kVariants[v].bk;
+    return true;
+}
 
 int gemm_bf16_variant_count() { return kNumVariants; }
 const char* gemm_bf16_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
