@@ -134,7 +134,7 @@ template <int NT, int A>
 __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatArg<NT, A> at,
                                                                const float* __restrict__ M,
                                                                const float* __restrict__ bias,
-                                                               float* __restrict__ y)
+                                                               float* __restrict__ y, int vec2)
 {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long long)g.K * g.P) return;
@@ -165,17 +165,41 @@ __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatAr
     }
     const float bv = bias ? bias[kk] : 0.f;
     float* yp = y + ((long long)img * g.K + kk) * g.Ho * g.Wo;
+    // A lane owns NT consecutive floats of NT output rows.  Stores of one float per lane would touch
+    // 64*NT*4/64 cache lines per instruction; pairs halve the number of store instructions.
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
         const int oy = ty * NT + i;
+        float o[NT];
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            const int ox = tx * NT + j;
             float acc = bv;
 #pragma unroll
             for (int b = 0; b < A; ++b) acc = fmaf(t[i][b], at.v[j][b], acc);
-            if (oy < g.Ho && ox < g.Wo) yp[(long long)oy * g.Wo + ox] = acc;
+            o[j] = acc;
         }
+        if (oy >= g.Ho) continue;
+        float* row = yp + (long long)oy * g.Wo + tx * NT;
+        if constexpr (NT == 4) {
+            if (vec2 == 2) {          // 16-byte aligned tile rows, no ragged column
+                *reinterpret_cast<float4*>(row) = make_float4(o[0], o[1], o[2], o[3]);
+                continue;
+            }
+        }
+        if constexpr (NT % 2 == 0) {
+            if (vec2) {
+#pragma unroll
+                for (int j = 0; j < NT; j += 2) {
+                    const int ox = tx * NT + j;
+                    if (ox + 1 < g.Wo) *reinterpret_cast<float2*>(row + j) = make_float2(o[j], o[j + 1]);
+                    else if (ox < g.Wo) row[j] = o[j];
+                }
+                continue;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+            if (tx * NT + j < g.Wo) row[j] = o[j];
     }
 }
 
@@ -206,7 +230,10 @@ hipError_t launch_output_t(const WinoGeom& g, const float* AT, const float* M, c
         for (int j = 0; j < A; ++j) m.v[i][j] = AT[i * A + j];
     const long long total = (long long)g.K * g.P;
     const unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL((output_transform_kernel<NT, A>), dim3(blocks), dim3(256), 0, s, g, m, M, bias, y);
+    // 8-byte stores need every tile row start 8-byte aligned: even n, even W_o, aligned base
+    int vec2 = (NT % 2 == 0) && (g.Wo % 2 == 0) && ((reinterpret_cast<uintptr_t>(y) & 7u) == 0);
+    if (NT == 4 && (g.Wo % 4 == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0)) vec2 = 2;   // whole-tile float4 rows
+    hipLaunchKernelGGL((output_transform_kernel<NT, A>), dim3(blocks), dim3(256), 0, s, g, m, M, bias, y, vec2);
     return hipGetLastError();
 }
 
