@@ -53,6 +53,10 @@ class ConvLayer:
         return (self.w + 2 * self.pad - self.dil * (self.kw - 1) - 1) // self.stride + 1
 
     @property
+    def out_shape(self) -> Tuple[int, int, int, int]:
+        return (self.n, self.c_out, self.h_out, self.w_out)
+
+    @property
     def direct_flops(self) -> int:
         """2*N*K*C*H_o*W_o*kh*kw: the direct-convolution count every scheme is priced in."""
         return 2 * self.n * self.c_out * self.c_in * self.h_out * self.w_out * self.kh * self.kw
@@ -108,6 +112,32 @@ def config_layers(cfg: int) -> List[ConvLayer]:
             _mk(5, 2, "mix64_112x112_k7", 16, 64, 112, 64, 7, 1, 3),
         ]
     raise ValueError(f"unknown workload config {cfg}")
+
+
+def chain_layers(kind: str, n: int = 1) -> List[ConvLayer]:
+    """Layers that feed one another (layer i+1 takes layer i's output), for the chained execution path.
+
+    ``resnet18_trunk``: the seven 3x3 layers of workload families 2/3 in network order -- a stride-1 layer at
+    each of the four resolutions with the stride-2 transition between them -- at batch ``n``.
+    ``small``: five small ragged layers (3x3, stride-2 3x3, 1x1, 5x5, unpadded 3x3) the oracle finishes quickly.
+    Only each layer's w and b are drawn (``draw``); x is drawn for the first layer alone.
+    """
+    if kind == "resnet18_trunk":
+        by_name = {l.name: l for l in config_layers(2)}
+        order = ["res64_56x56_k3", "res64to128_56x56_k3s2", "res128_28x28_k3", "res128to256_28x28_k3s2",
+                 "res256_14x14_k3", "res256to512_14x14_k3s2", "res512_7x7_k3"]
+        return [by_name[nm].with_batch(n) for nm in order]
+    if kind == "small":
+        def L(i, name, c, h, w, k, ksz, s, p):
+            return ConvLayer(name, n, c, h, w, k, ksz, ksz, s, p, 1, (-1.0, 1.0), BASE_SEED + 9500 + i)
+        return [
+            L(0, "ch0_k3", 5, 21, 18, 12, 3, 1, 1),        # -> 12 x 21 x 18
+            L(1, "ch1_k3s2", 12, 21, 18, 9, 3, 2, 1),      # -> 9 x 11 x 9
+            L(2, "ch2_pw", 9, 11, 9, 20, 1, 1, 0),         # -> 20 x 11 x 9
+            L(3, "ch3_k5", 20, 11, 9, 6, 5, 1, 2),         # -> 6 x 11 x 9
+            L(4, "ch4_k3nopad", 6, 11, 9, 7, 3, 1, 0),     # -> 7 x 9 x 7
+        ]
+    raise ValueError(f"unknown chain {kind!r}")
 
 
 CONFIG_TITLES: Dict[int, str] = {

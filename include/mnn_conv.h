@@ -249,6 +249,70 @@ int mnn_gemm_f32(const mnn_gemm_desc* desc, const float* At, const float* B, con
 int mnn_gemm_variant_count(int32_t prec);
 const char* mnn_gemm_variant_name(int32_t prec, int32_t variant);
 
+/*
+ * A chain of convolution layers prepared once and executed many times (Section 3.2,
+ * "preparation-execution decoupling", Table 2).  Layer i+1 consumes what layer i
+ * produces: its n, c_in, h, w must equal layer i's n, c_out, h_out, w_out.
+ *
+ * mnn_chain_create does all preparation: plans every layer as mnn_conv_plan does
+ * (same options, same caches), walks the chain once without running it to learn
+ * when each buffer is first and last needed (activation i: layers i and i+1; the
+ * Winograd-domain workspace of layer i: layer i only), places all of them in ONE
+ * device allocation with lifetime-based reuse, and allocates the prepared weights.
+ * After it returns, no call below allocates or frees device memory.
+ *
+ * mnn_chain_set_weights prepares layer i's weights (device, float32, KCRS; bias
+ * device or NULL) on `stream`; the chain keeps U / the transposed weights and a
+ * copy of the bias, the caller's buffers may be released once `stream` has run.
+ *
+ * mnn_chain_run enqueues every kernel of every layer on `stream` (input: layer 0's
+ * NCHW tensor, output: the last layer's; both device, caller-owned).
+ * mnn_chain_capture records the same launches for fixed input/output addresses
+ * into a HIP graph (on a stream the chain owns; nothing executes), and
+ * mnn_chain_replay launches that graph on `stream` -- the analogue of a
+ * pre-recorded command buffer.  A chain must not run on two streams at once.
+ * Errors: MNN_E_INVALID_ARG (shapes that do not connect, NULL pointers, weights
+ * not set, replay without capture), MNN_E_HIP, MNN_E_OOM, MNN_E_NO_DEVICE.
+ */
+typedef struct mnn_chain_s* mnn_chain_t;
+typedef struct {
+    mnn_conv_shape shape;
+    mnn_conv_geom geom;
+} mnn_chain_layer;
+typedef struct {
+    int32_t n_layers;
+    int32_t kernels_per_run;     /* launches of one mnn_chain_run */
+    int32_t graph_nodes;         /* nodes of the captured graph, 0 before mnn_chain_capture */
+    int32_t reserved;
+    uint64_t arena_bytes;        /* the one allocation: activations + workspaces with reuse */
+    uint64_t unshared_bytes;     /* the same buffers without reuse (sum of their sizes) */
+    uint64_t live_peak_bytes;    /* most bytes alive at any layer: lower bound for arena_bytes */
+    uint64_t weight_bytes;       /* prepared weights, bias copies, split-K counters */
+} mnn_chain_info_t;
+
+int mnn_chain_create(const mnn_chain_layer* layers, int32_t n_layers, const mnn_conv_options* options,
+                     void* stream, mnn_chain_t* out_chain);
+int mnn_chain_set_weights(mnn_chain_t chain, int32_t layer, const float* weight, const float* bias, void* stream);
+int mnn_chain_run(mnn_chain_t chain, const float* input, float* output, void* stream);
+int mnn_chain_capture(mnn_chain_t chain, const float* input, float* output);
+int mnn_chain_replay(mnn_chain_t chain, void* stream);
+int mnn_chain_info(mnn_chain_t chain, mnn_chain_info_t* out);
+int mnn_chain_layer_scheme(mnn_chain_t chain, int32_t layer, mnn_scheme* out);
+int mnn_chain_layer_describe(mnn_chain_t chain, int32_t layer, char* buf, size_t cap);
+/* Copies intermediate activation `layer` (the output of that layer, layer < n_layers-1) to host memory
+ * after synchronising `stream`; valid only until the next run overwrites it.  For tests. */
+int mnn_chain_read_activation(mnn_chain_t chain, int32_t layer, float* dst, size_t bytes, void* stream);
+void mnn_chain_destroy(mnn_chain_t chain);
+
+/*
+ * The pool planner on its own.  Host only.  Buffer i has bytes[i] >= 0 bytes and is
+ * alive from operator first[i] to operator last[i] inclusive.  Writes offsets[i]
+ * (multiples of align, a power of two) such that buffers alive at the same time
+ * never overlap, and the pool size to *total.
+ */
+int mnn_arena_plan(const int64_t* bytes, const int32_t* first, const int32_t* last, int32_t count,
+                   int64_t align, int64_t* offsets, int64_t* total);
+
 /* Process-wide cache of planner choices keyed by device, shape, geometry and options. */
 int mnn_conv_cache_size(void);
 void mnn_conv_cache_clear(void);

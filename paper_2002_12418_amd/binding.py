@@ -59,6 +59,16 @@ class _Info(ctypes.Structure):
     _fields_ = [(n, c_int32) for n in ("alpha", "tile_n", "tiles_h", "tiles_w", "p", "ldp", "ldk", "kg", "pg", "h_out", "w_out")]
 
 
+class _ChainLayer(ctypes.Structure):
+    _fields_ = [("shape", _Shape), ("geom", _Geom)]
+
+
+class _ChainInfo(ctypes.Structure):
+    _fields_ = [("n_layers", c_int32), ("kernels_per_run", c_int32), ("graph_nodes", c_int32), ("reserved", c_int32),
+                ("arena_bytes", ctypes.c_uint64), ("unshared_bytes", ctypes.c_uint64),
+                ("live_peak_bytes", ctypes.c_uint64), ("weight_bytes", ctypes.c_uint64)]
+
+
 def _load() -> ctypes.CDLL:
     if not os.path.exists(_LIB_PATH):
         # build once if nothing is built; a missing toolchain is a hard error
@@ -95,6 +105,19 @@ def _load() -> ctypes.CDLL:
     L.mnn_gemm_variant_count.argtypes = [c_int32]
     L.mnn_gemm_variant_name.argtypes = [c_int32, c_int32]
     L.mnn_gemm_variant_name.restype = c_char_p
+    L.mnn_chain_create.argtypes = [POINTER(_ChainLayer), c_int32, POINTER(_Options), vp, POINTER(vp)]
+    L.mnn_chain_set_weights.argtypes = [vp, c_int32, vp, vp, vp]
+    L.mnn_chain_run.argtypes = [vp, vp, vp, vp]
+    L.mnn_chain_capture.argtypes = [vp, vp, vp]
+    L.mnn_chain_replay.argtypes = [vp, vp]
+    L.mnn_chain_info.argtypes = [vp, POINTER(_ChainInfo)]
+    L.mnn_chain_layer_scheme.argtypes = [vp, c_int32, POINTER(_Scheme)]
+    L.mnn_chain_layer_describe.argtypes = [vp, c_int32, ctypes.c_char_p, c_size_t]
+    L.mnn_chain_read_activation.argtypes = [vp, c_int32, vp, c_size_t, vp]
+    L.mnn_chain_destroy.argtypes = [vp]
+    L.mnn_chain_destroy.restype = None
+    L.mnn_arena_plan.argtypes = [POINTER(ctypes.c_int64), POINTER(c_int32), POINTER(c_int32), c_int32, ctypes.c_int64,
+                                 POINTER(ctypes.c_int64), POINTER(ctypes.c_int64)]
     L.mnn_conv_cache_size.argtypes = []
     L.mnn_conv_cache_clear.argtypes = []
     L.mnn_conv_cache_clear.restype = None
@@ -355,6 +378,113 @@ class ConvPlan:
         if getattr(self, "_h", None) is not None and self._h.value:
             lib.mnn_conv_plan_destroy(self._h)
             self._h = c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+
+def arena_plan(sizes: Sequence[int], first: Sequence[int], last: Sequence[int], align: int = 256):
+    """mnn_arena_plan: (offsets, total) for buffers alive over operators first[i]..last[i]."""
+    n = len(sizes)
+    if len(first) != n or len(last) != n:
+        raise ValueError("sizes, first and last must have the same length")
+    sz = (ctypes.c_int64 * max(n, 1))(*sizes)
+    fi = (c_int32 * max(n, 1))(*first)
+    la = (c_int32 * max(n, 1))(*last)
+    off = (ctypes.c_int64 * max(n, 1))()
+    tot = ctypes.c_int64()
+    _check(lib.mnn_arena_plan(sz, fi, la, n, align, off, byref(tot)))
+    return [int(off[i]) for i in range(n)], int(tot.value)
+
+
+class ConvChain:
+    """mnn_chain_*: a chain of layers planned once, one arena, eager run or HIP-graph replay."""
+
+    def __init__(self, layers, options: Optional[Options] = None, stream=None):
+        self._h = c_void_p()
+        self.layers = list(layers)
+        arr = (_ChainLayer * max(len(self.layers), 1))()
+        for i, l in enumerate(self.layers):
+            s, g = _shape_geom(l.n, l.c_in, l.h, l.w, l.c_out, l.kh, l.kw, l.stride, l.pad, l.dil)
+            arr[i].shape, arr[i].geom = s, g
+        o = options._c() if options else None
+        _check(lib.mnn_chain_create(arr, len(self.layers), byref(o) if o else None, _stream_handle(stream),
+                                    byref(self._h)))
+        self._keep = None
+
+    @property
+    def info(self) -> dict:
+        c = _ChainInfo()
+        _check(lib.mnn_chain_info(self._h, byref(c)))
+        return {f: int(getattr(c, f)) for f, _ in _ChainInfo._fields_ if f != "reserved"}
+
+    def scheme(self, layer: int) -> Scheme:
+        c = _Scheme()
+        _check(lib.mnn_chain_layer_scheme(self._h, layer, byref(c)))
+        return Scheme._from(c)
+
+    def describe(self, layer: int) -> str:
+        buf = ctypes.create_string_buffer(256)
+        _check(lib.mnn_chain_layer_describe(self._h, layer, buf, 256))
+        return buf.value.decode()
+
+    @staticmethod
+    def _dev_f32(t, shape, name):
+        import torch
+        if tuple(t.shape) != tuple(shape) or t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError(f"{name}: expected contiguous float32 device tensor of shape {tuple(shape)}, got {tuple(t.shape)} {t.dtype}")
+
+    def set_weights(self, layer: int, w, b=None, stream=None):
+        l = self.layers[layer]
+        self._dev_f32(w, (l.c_out, l.c_in, l.kh, l.kw), "weight")
+        if b is not None:
+            self._dev_f32(b, (l.c_out,), "bias")
+        _check(lib.mnn_chain_set_weights(self._h, layer, w.data_ptr(), b.data_ptr() if b is not None else None,
+                                         _stream_handle(stream)))
+
+    def _io(self, x, y):
+        import torch
+        l0, ln = self.layers[0], self.layers[-1]
+        self._dev_f32(x, (l0.n, l0.c_in, l0.h, l0.w), "input")
+        if y is None:
+            y = torch.empty(ln.out_shape, dtype=torch.float32, device=x.device)
+        self._dev_f32(y, ln.out_shape, "output")
+        return y
+
+    def run(self, x, y=None, stream=None):
+        y = self._io(x, y)
+        _check(lib.mnn_chain_run(self._h, x.data_ptr(), y.data_ptr(), _stream_handle(stream)))
+        return y
+
+    def capture(self, x, y=None):
+        y = self._io(x, y)
+        _check(lib.mnn_chain_capture(self._h, x.data_ptr(), y.data_ptr()))
+        self._keep = (x, y)          # the graph holds these addresses
+        return y
+
+    def replay(self, stream=None):
+        _check(lib.mnn_chain_replay(self._h, _stream_handle(stream)))
+
+    def activation_to_numpy(self, layer: int, stream=None) -> np.ndarray:
+        l = self.layers[layer]
+        out = np.empty(l.out_shape, dtype=np.float32)
+        _check(lib.mnn_chain_read_activation(self._h, layer, out.ctypes.data, out.nbytes, _stream_handle(stream)))
+        return out
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib.mnn_chain_destroy(self._h)
+            self._h = c_void_p()
+        self._keep = None
 
     def __del__(self):
         try:

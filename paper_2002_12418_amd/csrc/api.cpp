@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <string>
@@ -15,6 +16,7 @@
 
 #include "../../include/mnn_conv.h"
 #include "cook_toom_gen.hpp"
+#include "arena.hpp"
 #include "kernels.hpp"
 
 using namespace mnnconv;
@@ -233,6 +235,17 @@ int time_gemm(const GemmProblem& p, hipStream_t s, hipEvent_t e0, hipEvent_t e1,
     return MNN_OK;
 }
 
+bool cached_gemm_choice(const GemmProblem& p, GemmChoice* out)
+{
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    std::lock_guard<std::mutex> lk(g_gemm_mu);
+    auto it = g_gemm_choice.find(gemm_key(dev, p));
+    if (it == g_gemm_choice.end()) return false;
+    *out = it->second;
+    return true;
+}
+
 // Times every usable tile configuration -- and, where the tiles do not fill the chip, every useful
 // split of the reduction -- on the given (valid, writable) buffers; returns the fastest.
 int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
@@ -308,6 +321,9 @@ struct Impl {
     int gemm_splitk = 1;       // workgroups per tile along the reduction
     float* sk_partial = nullptr; size_t sk_partial_bytes = 0;
     unsigned* sk_counters = nullptr; size_t sk_counters_bytes = 0;
+    // V, M and the split-K partials hold nothing between two runs.  A plan on its own allocates them;
+    // a chain of layers binds them to a region of its arena instead (bind_transient).
+    bool transient_external = false;
 
     ~Impl() { release(); }
     Impl() = default;
@@ -317,9 +333,11 @@ struct Impl {
     void release()
     {
         if (U) (void)hipFree(U);
-        if (V) (void)hipFree(V);
-        if (M) (void)hipFree(M);
-        if (sk_partial) (void)hipFree(sk_partial);
+        if (!transient_external) {
+            if (V) (void)hipFree(V);
+            if (M) (void)hipFree(M);
+            if (sk_partial) (void)hipFree(sk_partial);
+        }
         if (sk_counters) (void)hipFree(sk_counters);
         U = V = M = nullptr;
         sk_partial = nullptr;
@@ -339,10 +357,26 @@ struct Impl {
         return MNN_OK;
     }
 
-    int prepare(const Layer& layer, const mnn_scheme& s, const mnn_conv_options& o)
+    int alloc_transient(float** p, size_t bytes, const char* what)
+    {
+        if (transient_external) { *p = nullptr; return MNN_OK; }
+        return alloc_zero(p, bytes, what);
+    }
+
+    static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+    size_t transient_bytes() const { return align256(V_bytes) + align256(M_bytes) + align256(sk_partial_bytes); }
+    void bind_transient(char* base)
+    {
+        V = V_bytes ? reinterpret_cast<float*>(base) : nullptr;
+        M = M_bytes ? reinterpret_cast<float*>(base + align256(V_bytes)) : nullptr;
+        sk_partial = sk_partial_bytes ? reinterpret_cast<float*>(base + align256(V_bytes) + align256(M_bytes)) : nullptr;
+    }
+
+    int prepare(const Layer& layer, const mnn_scheme& s, const mnn_conv_options& o, bool external_transient = false)
     {
         L = layer;
         scheme = s;
+        transient_external = external_transient;
         const mnn_conv_shape& sh = L.s;
         ldk = round_up(sh.c_out, 4);
         if (s.prec != MNN_GEMM_FP32 && s.kind == MNN_SCHEME_WINOGRAD && s.variant != MNN_WINO_UNFUSED)
@@ -376,7 +410,7 @@ struct Impl {
                 if (V_bytes >= ((size_t)1 << 40) || U_bytes >= ((size_t)1 << 40))
                     return fail(MNN_E_UNSUPPORTED, "Winograd-domain tensors too large");
                 if ((rc = alloc_zero(&U, U_bytes, "hipMalloc U"))) return rc;
-                if ((rc = alloc_zero(&V, V_bytes, "hipMalloc V"))) return rc;
+                if ((rc = alloc_transient(&V, V_bytes, "hipMalloc V"))) return rc;
                 return MNN_OK;
             }
             if ((long long)wg.C * wg.ldp >= (1ll << 31) || (long long)wg.K * wg.ldp >= (1ll << 31))
@@ -385,8 +419,8 @@ struct Impl {
             V_bytes = a2 * sh.c_in * wg.ldp * sizeof(float);
             M_bytes = a2 * sh.c_out * wg.ldp * sizeof(float);
             if ((rc = alloc_zero(&U, U_bytes, "hipMalloc U"))) return rc;
-            if ((rc = alloc_zero(&V, V_bytes, "hipMalloc V"))) return rc;
-            if ((rc = alloc_zero(&M, M_bytes, "hipMalloc M"))) return rc;
+            if ((rc = alloc_transient(&V, V_bytes, "hipMalloc V"))) return rc;
+            if ((rc = alloc_transient(&M, M_bytes, "hipMalloc M"))) return rc;
             return MNN_OK;
         }
         if (s.kind == MNN_SCHEME_GEMM1X1) {
@@ -474,7 +508,7 @@ struct Impl {
         gemm_splitk_workspace(p, bm, bn, gemm_splitk, &pf, &cn);
         sk_partial_bytes = (size_t)pf * sizeof(float);
         sk_counters_bytes = (size_t)cn * sizeof(unsigned);
-        int rc = alloc_zero(&sk_partial, sk_partial_bytes, "hipMalloc split-K partials");
+        int rc = alloc_transient(&sk_partial, sk_partial_bytes, "hipMalloc split-K partials");
         if (rc) return rc;
         float* c32 = nullptr;
         rc = alloc_zero(&c32, sk_counters_bytes, "hipMalloc split-K counters");
@@ -485,8 +519,14 @@ struct Impl {
     int tune(hipStream_t s)
     {
         GemmChoice c{0, 1};
+        static const float dummy_bias = 0.f;      // only "is there a bias" enters the cache key
         if (scheme.kind == MNN_SCHEME_WINOGRAD && scheme.variant == MNN_WINO_UNFUSED) {
             const GemmProblem p = wino_gemm_problem();
+            if (transient_external) {
+                // V and M are not bound yet: take the remembered choice, else the shape heuristic
+                if (!cached_gemm_choice(p, &c)) c = GemmChoice{0, 1};
+                return adopt(p, c);
+            }
             int rc = tune_gemm(p, s, &c);
             return rc ? rc : adopt(p, c);
         }
@@ -497,6 +537,12 @@ struct Impl {
             float *tx = nullptr, *ty = nullptr, *tb = nullptr;
             hipError_t e;
             int rc = MNN_OK;
+            {
+                // a shape tuned before needs no scratch tensors (the key holds no addresses)
+                const GemmProblem q = scheme.kind == MNN_SCHEME_DIRECT ? direct_gemm_problem(nullptr, &dummy_bias, nullptr)
+                                                                       : pointwise_gemm_problem(nullptr, &dummy_bias, nullptr);
+                if (cached_gemm_choice(q, &c)) return adopt(q, c);
+            }
             if ((e = hipMalloc((void**)&tx, xb)) != hipSuccess || (e = hipMalloc((void**)&ty, yb)) != hipSuccess ||
                 (e = hipMalloc((void**)&tb, (size_t)sh.c_out * sizeof(float))) != hipSuccess)
                 rc = fail_hip(e, "hipMalloc tuning scratch");
@@ -560,6 +606,24 @@ struct Impl {
     size_t bytes() const { return U_bytes + V_bytes + M_bytes + sk_partial_bytes + sk_counters_bytes; }
 };
 
+void describe_impl(const Impl& im, char* buf, size_t cap)
+{
+    std::string gvs = gemm_variant_name(im.scheme.prec, im.gemm_variant) ? gemm_variant_name(im.scheme.prec, im.gemm_variant) : "?";
+    if (im.gemm_splitk > 1) gvs += " splitk=" + std::to_string(im.gemm_splitk);
+    const char* gv = gvs.c_str();
+    switch (im.scheme.kind) {
+        case MNN_SCHEME_WINOGRAD:
+            if (im.scheme.variant == MNN_WINO_UNFUSED)
+                std::snprintf(buf, cap, "F(%d,%d) unfused gemm=%s", im.wg.n, im.wg.k, gv);
+            else
+                std::snprintf(buf, cap, "F(%d,%d) fused-output %s", im.wg.n, im.wg.k,
+                              im.scheme.variant == MNN_WINO_FUSED_OUT_32 ? "32x32" : "64x64");
+            break;
+        case MNN_SCHEME_GEMM1X1: std::snprintf(buf, cap, "gemm1x1 gemm=%s", gv); break;
+        default: std::snprintf(buf, cap, "sliding-window implicit gemm=%s", gv); break;
+    }
+}
+
 // ------------------------------------------------------------------ choice cache
 using CacheKey = std::tuple<int, std::vector<int>, float>;
 std::mutex g_cache_mu;
@@ -584,6 +648,58 @@ struct mnn_conv_plan_s {
     const float* cached_weight = nullptr;
     bool weights_valid = false;
     bool from_cache = false;
+};
+
+
+struct mnn_chain_s {
+    std::vector<Layer> layers;
+    mnn_conv_options opt{};
+    int device = 0;
+    std::vector<std::unique_ptr<Impl>> impls;
+    std::vector<float*> bias;            // chain-owned copies (c_out floats each)
+    std::vector<char> has_bias, weights_set;
+    char* arena = nullptr;
+    size_t arena_bytes = 0, unshared_bytes = 0, live_peak_bytes = 0, weight_bytes = 0;
+    std::vector<long long> act_off, ws_off;     // activation i = output of layer i (i < n-1); workspace of layer i
+    std::vector<size_t> act_bytes;
+    hipStream_t capture_stream = nullptr;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    size_t graph_nodes = 0;
+
+    ~mnn_chain_s()
+    {
+        if (exec) (void)hipGraphExecDestroy(exec);
+        if (graph) (void)hipGraphDestroy(graph);
+        if (capture_stream) (void)hipStreamDestroy(capture_stream);
+        impls.clear();
+        for (float* b : bias)
+            if (b) (void)hipFree(b);
+        if (arena) (void)hipFree(arena);
+    }
+
+    int kernels_per_run() const
+    {
+        int k = 0;
+        for (const auto& im : impls)
+            for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st) k += im->has_stage(st) ? 1 : 0;
+        return k;
+    }
+
+    int enqueue(const float* input, float* output, hipStream_t s)
+    {
+        const int n = (int)impls.size();
+        for (int i = 0; i < n; ++i) {
+            const float* x = i == 0 ? input : reinterpret_cast<const float*>(arena + act_off[i - 1]);
+            float* y = i == n - 1 ? output : reinterpret_cast<float*>(arena + act_off[i]);
+            const float* b = has_bias[i] ? bias[i] : nullptr;
+            for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st) {
+                int rc = impls[i]->run_stage(st, x, nullptr, b, y, s);
+                if (rc) return rc;
+            }
+        }
+        return MNN_OK;
+    }
 };
 
 namespace {
@@ -782,21 +898,7 @@ int mnn_conv_plan_candidates(mnn_conv_plan_t plan, mnn_scheme* out, int32_t cap,
 int mnn_conv_plan_describe(mnn_conv_plan_t plan, char* buf, size_t cap)
 {
     if (!plan || !buf || cap == 0) return fail(MNN_E_INVALID_ARG, "bad argument");
-    const Impl& im = plan->impl;
-    std::string gvs = gemm_variant_name(im.scheme.prec, im.gemm_variant) ? gemm_variant_name(im.scheme.prec, im.gemm_variant) : "?";
-    if (im.gemm_splitk > 1) gvs += " splitk=" + std::to_string(im.gemm_splitk);
-    const char* gv = gvs.c_str();
-    switch (im.scheme.kind) {
-        case MNN_SCHEME_WINOGRAD:
-            if (im.scheme.variant == MNN_WINO_UNFUSED)
-                std::snprintf(buf, cap, "F(%d,%d) unfused gemm=%s", im.wg.n, im.wg.k, gv ? gv : "?");
-            else
-                std::snprintf(buf, cap, "F(%d,%d) fused-output %s", im.wg.n, im.wg.k,
-                              im.scheme.variant == MNN_WINO_FUSED_OUT_32 ? "32x32" : "64x64");
-            break;
-        case MNN_SCHEME_GEMM1X1: std::snprintf(buf, cap, "gemm1x1 gemm=%s", gv ? gv : "?"); break;
-        default: std::snprintf(buf, cap, "sliding-window implicit gemm=%s", gv ? gv : "?"); break;
-    }
+    describe_impl(plan->impl, buf, cap);
     return MNN_OK;
 }
 
@@ -1108,5 +1210,252 @@ int mnn_conv_cache_load(const char* path)
 const char* mnn_last_error(void) { return g_err.c_str(); }
 
 int mnn_version(void) { return 100; }
+
+}  // extern "C"
+
+// ------------------------------------------------------------------ chain of layers
+namespace {
+
+int chain_create_impl(const mnn_chain_layer* layers, int32_t n_layers, const mnn_conv_options* options, void* stream,
+                      mnn_chain_t* out_chain)
+{
+    if (!out_chain) return fail(MNN_E_INVALID_ARG, "out_chain must not be NULL");
+    *out_chain = nullptr;
+    if (!layers || n_layers <= 0 || n_layers > 4096) return fail(MNN_E_INVALID_ARG, "layers must not be NULL, 1 <= n_layers <= 4096");
+    mnn_conv_options o;
+    int rc = validate_options(options, &o);
+    if (rc) return rc;
+    std::unique_ptr<mnn_chain_s> ch(new mnn_chain_s());
+    ch->opt = o;
+    for (int i = 0; i < n_layers; ++i) {
+        Layer L;
+        if ((rc = validate(&layers[i].shape, &layers[i].geom, &L))) return rc;
+        if (i > 0) {
+            const Layer& p = ch->layers.back();
+            if (L.s.n != p.s.n || L.s.c_in != p.s.c_out || L.s.h != p.Ho || L.s.w != p.Wo)
+                return fail(MNN_E_INVALID_ARG, "layer %d takes [%d,%d,%d,%d] but layer %d produces [%d,%d,%d,%d]", i, L.s.n,
+                            L.s.c_in, L.s.h, L.s.w, i - 1, p.s.n, p.s.c_out, p.Ho, p.Wo);
+        }
+        ch->layers.push_back(L);
+    }
+    // pre-inference per layer: an ordinary plan times the candidates (or finds them cached) and leaves
+    // the scheme and the GEMM configuration in the caches; its own workspace is released again
+    std::vector<mnn_scheme> chosen(n_layers);
+    for (int i = 0; i < n_layers; ++i) {
+        mnn_conv_plan_t pl = nullptr;
+        if ((rc = plan_impl(&layers[i].shape, &layers[i].geom, &o, stream, &pl))) return rc;
+        chosen[i] = pl->impl.scheme;
+        delete pl;
+    }
+    hipError_t e = hipGetDevice(&ch->device);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    const int n = n_layers;
+    ch->bias.assign(n, nullptr);
+    ch->has_bias.assign(n, 0);
+    ch->weights_set.assign(n, 0);
+    for (int i = 0; i < n; ++i) {
+        ch->impls.emplace_back(new Impl());
+        Impl& im = *ch->impls.back();
+        if ((rc = im.prepare(ch->layers[i], chosen[i], o, /*external_transient=*/true))) return rc;
+        if ((rc = im.tune((hipStream_t)stream))) return rc;
+        const size_t bb = (size_t)ch->layers[i].s.c_out * sizeof(float);
+        if ((e = hipMalloc((void**)&ch->bias[i], bb)) != hipSuccess) return fail_hip(e, "hipMalloc bias");
+        ch->weight_bytes += im.U_bytes + im.sk_counters_bytes + bb;
+    }
+    // the virtual walk: activation i lives over layers i and i+1, workspace i over layer i
+    std::vector<ArenaBuffer> bufs;
+    ch->act_bytes.assign(n, 0);
+    for (int i = 0; i + 1 < n; ++i) {
+        const Layer& L = ch->layers[i];
+        ch->act_bytes[i] = (size_t)L.s.n * L.s.c_out * L.Ho * L.Wo * sizeof(float);
+        bufs.push_back(ArenaBuffer{(long long)ch->act_bytes[i], i, i + 1});
+    }
+    for (int i = 0; i < n; ++i) bufs.push_back(ArenaBuffer{(long long)ch->impls[i]->transient_bytes(), i, i});
+    std::vector<long long> off;
+    long long total = 0;
+    if (!plan_arena(bufs, 256, &off, &total)) return fail(MNN_E_INVALID_ARG, "arena planning failed");
+    ch->act_off.assign(off.begin(), off.begin() + (n - 1));
+    ch->ws_off.assign(off.begin() + (n - 1), off.end());
+    ch->arena_bytes = (size_t)total;
+    std::vector<long long> live(n, 0);
+    for (const ArenaBuffer& b : bufs) {
+        const long long sz = (b.bytes + 255) / 256 * 256;
+        ch->unshared_bytes += (size_t)sz;
+        for (int t = b.first; t <= b.last; ++t) live[t] += sz;
+    }
+    ch->live_peak_bytes = (size_t)*std::max_element(live.begin(), live.end());
+    if (total > 0) {
+        if ((e = hipMalloc((void**)&ch->arena, (size_t)total)) != hipSuccess) return fail_hip(e, "hipMalloc arena");
+        if ((e = hipMemset(ch->arena, 0, (size_t)total)) != hipSuccess) return fail_hip(e, "hipMemset arena");
+        if ((e = hipDeviceSynchronize()) != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
+    }
+    for (int i = 0; i < n; ++i) ch->impls[i]->bind_transient(ch->arena + ch->ws_off[i]);
+    *out_chain = ch.release();
+    return MNN_OK;
+}
+
+int chain_check(mnn_chain_t ch, int32_t layer)
+{
+    if (!ch) return fail(MNN_E_INVALID_ARG, "chain is NULL");
+    if (layer < 0 || layer >= (int)ch->impls.size()) return fail(MNN_E_INVALID_ARG, "layer %d out of range", layer);
+    return MNN_OK;
+}
+
+int chain_ready(mnn_chain_t ch)
+{
+    if (!ch) return fail(MNN_E_INVALID_ARG, "chain is NULL");
+    for (size_t i = 0; i < ch->weights_set.size(); ++i)
+        if (!ch->weights_set[i]) return fail(MNN_E_INVALID_ARG, "weights of layer %d have not been set", (int)i);
+    return MNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mnn_chain_create(const mnn_chain_layer* layers, int32_t n_layers, const mnn_conv_options* options, void* stream,
+                     mnn_chain_t* out_chain)
+{
+    try {
+        return chain_create_impl(layers, n_layers, options, stream, out_chain);
+    } catch (const std::bad_alloc&) {
+        return fail(MNN_E_OOM, "host allocation failed");
+    } catch (...) {
+        return fail(MNN_E_INVALID_ARG, "unexpected exception in mnn_chain_create");
+    }
+}
+
+int mnn_chain_set_weights(mnn_chain_t ch, int32_t layer, const float* weight, const float* bias, void* stream)
+{
+    int rc = chain_check(ch, layer);
+    if (rc) return rc;
+    if (!weight) return fail(MNN_E_INVALID_ARG, "weight must not be NULL");
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = ch->impls[layer]->run_stage(MNN_STAGE_FILTER, nullptr, weight, nullptr, nullptr, s))) return rc;
+    if (bias) {
+        hipError_t e = hipMemcpyAsync(ch->bias[layer], bias, (size_t)ch->layers[layer].s.c_out * sizeof(float),
+                                      hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return fail_hip(e, "hipMemcpyAsync bias");
+    }
+    ch->has_bias[layer] = bias ? 1 : 0;
+    ch->weights_set[layer] = 1;
+    return MNN_OK;
+}
+
+int mnn_chain_run(mnn_chain_t ch, const float* input, float* output, void* stream)
+{
+    int rc = chain_ready(ch);
+    if (rc) return rc;
+    if (!input || !output) return fail(MNN_E_INVALID_ARG, "input and output must not be NULL");
+    return ch->enqueue(input, output, (hipStream_t)stream);
+}
+
+int mnn_chain_capture(mnn_chain_t ch, const float* input, float* output)
+{
+    int rc = chain_ready(ch);
+    if (rc) return rc;
+    if (!input || !output) return fail(MNN_E_INVALID_ARG, "input and output must not be NULL");
+    hipError_t e;
+    if (!ch->capture_stream &&
+        (e = hipStreamCreateWithFlags(&ch->capture_stream, hipStreamNonBlocking)) != hipSuccess)
+        return fail_hip(e, "hipStreamCreateWithFlags");
+    if (ch->exec) { (void)hipGraphExecDestroy(ch->exec); ch->exec = nullptr; }
+    if (ch->graph) { (void)hipGraphDestroy(ch->graph); ch->graph = nullptr; }
+    ch->graph_nodes = 0;
+    if ((e = hipStreamBeginCapture(ch->capture_stream, hipStreamCaptureModeThreadLocal)) != hipSuccess)
+        return fail_hip(e, "hipStreamBeginCapture");
+    rc = ch->enqueue(input, output, ch->capture_stream);
+    hipGraph_t g = nullptr;
+    e = hipStreamEndCapture(ch->capture_stream, &g);
+    if (rc) {
+        if (g) (void)hipGraphDestroy(g);
+        return rc;
+    }
+    if (e != hipSuccess || !g) return fail_hip(e, "hipStreamEndCapture");
+    ch->graph = g;
+    if ((e = hipGraphInstantiate(&ch->exec, g, nullptr, nullptr, 0)) != hipSuccess) {
+        ch->exec = nullptr;
+        return fail_hip(e, "hipGraphInstantiate");
+    }
+    size_t nodes = 0;
+    if (hipGraphGetNodes(g, nullptr, &nodes) == hipSuccess) ch->graph_nodes = nodes;
+    return MNN_OK;
+}
+
+int mnn_chain_replay(mnn_chain_t ch, void* stream)
+{
+    if (!ch) return fail(MNN_E_INVALID_ARG, "chain is NULL");
+    if (!ch->exec) return fail(MNN_E_INVALID_ARG, "mnn_chain_capture has not been called");
+    hipError_t e = hipGraphLaunch(ch->exec, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "hipGraphLaunch");
+    return MNN_OK;
+}
+
+int mnn_chain_info(mnn_chain_t ch, mnn_chain_info_t* out)
+{
+    if (!ch || !out) return fail(MNN_E_INVALID_ARG, "NULL argument");
+    std::memset(out, 0, sizeof *out);
+    out->n_layers = (int32_t)ch->impls.size();
+    out->kernels_per_run = ch->kernels_per_run();
+    out->graph_nodes = (int32_t)ch->graph_nodes;
+    out->arena_bytes = ch->arena_bytes;
+    out->unshared_bytes = ch->unshared_bytes;
+    out->live_peak_bytes = ch->live_peak_bytes;
+    out->weight_bytes = ch->weight_bytes;
+    return MNN_OK;
+}
+
+int mnn_chain_layer_scheme(mnn_chain_t ch, int32_t layer, mnn_scheme* out)
+{
+    int rc = chain_check(ch, layer);
+    if (rc) return rc;
+    if (!out) return fail(MNN_E_INVALID_ARG, "out is NULL");
+    *out = ch->impls[layer]->scheme;
+    return MNN_OK;
+}
+
+int mnn_chain_layer_describe(mnn_chain_t ch, int32_t layer, char* buf, size_t cap)
+{
+    int rc = chain_check(ch, layer);
+    if (rc) return rc;
+    if (!buf || cap == 0) return fail(MNN_E_INVALID_ARG, "bad argument");
+    describe_impl(*ch->impls[layer], buf, cap);
+    return MNN_OK;
+}
+
+int mnn_chain_read_activation(mnn_chain_t ch, int32_t layer, float* dst, size_t bytes, void* stream)
+{
+    int rc = chain_check(ch, layer);
+    if (rc) return rc;
+    if (layer + 1 >= (int)ch->impls.size()) return fail(MNN_E_INVALID_ARG, "the last layer writes to the caller's output");
+    if (!dst || bytes > ch->act_bytes[layer]) return fail(MNN_E_INVALID_ARG, "dst NULL or more bytes than the activation holds");
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+    if ((e = hipMemcpy(dst, ch->arena + ch->act_off[layer], bytes, hipMemcpyDeviceToHost)) != hipSuccess)
+        return fail_hip(e, "hipMemcpy");
+    return MNN_OK;
+}
+
+void mnn_chain_destroy(mnn_chain_t ch) { delete ch; }
+
+int mnn_arena_plan(const int64_t* bytes, const int32_t* first, const int32_t* last, int32_t count, int64_t align,
+                   int64_t* offsets, int64_t* total)
+{
+    if (count < 0 || !total || (count > 0 && (!bytes || !first || !last || !offsets)))
+        return fail(MNN_E_INVALID_ARG, "NULL argument or negative count");
+    try {
+        std::vector<ArenaBuffer> bufs(count);
+        for (int i = 0; i < count; ++i) bufs[i] = ArenaBuffer{(long long)bytes[i], first[i], last[i]};
+        std::vector<long long> off;
+        long long tot = 0;
+        if (!plan_arena(bufs, (long long)align, &off, &tot))
+            return fail(MNN_E_INVALID_ARG, "need bytes >= 0, 0 <= first <= last and align a power of two");
+        for (int i = 0; i < count; ++i) offsets[i] = off[i];
+        *total = tot;
+        return MNN_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(MNN_E_OOM, "host allocation failed");
+    }
+}
 
 }  // extern "C"

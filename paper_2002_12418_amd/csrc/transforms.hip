@@ -72,7 +72,15 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg
         if (rest >= (long long)g.cchunks * pgroups) return;
         p = (int)(rest % pgroups) * 16 + (int)(idx & 15);
         c = (int)(rest / pgroups) * 4 + (int)((idx >> 4) & 3);
-        if (p >= g.P || c >= g.C) return;
+        if (p >= g.P || c >= g.C) {
+            // padding of the blocked layout: the multiply stage reads it (against zero rows of U for
+            // padded channels), so it must hold finite values whatever the memory held before
+            float* vz = V + (((long long)(c >> 2) * A * g.pg + (p >> 4)) << 6) + ((c & 3) << 4) + (p & 15);
+            const long long zi = (long long)g.pg * 64, zj = (long long)g.cchunks * A * g.pg * 64;
+            for (int i = 0; i < A; ++i)
+                for (int j = 0; j < A; ++j) vz[i * zi + j * zj] = 0.f;
+            return;
+        }
     } else {
         if (idx >= (long long)g.C * g.P) return;
         c = (int)(idx / g.P);
