@@ -149,6 +149,57 @@ def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
     return res
 
 
+def run_chain(kind, batch, steps, warmup, stream, mnn, torch):
+    """Chained execution of `kind` at `batch`: the same layers run (a) one plan at a time, each with memory of
+    its own, (b) as one chain sharing an arena, launched kernel by kernel, (c) as the chain's captured HIP graph."""
+    from conv_workloads import chain_layers, draw
+    layers = chain_layers(kind, batch)
+    x = torch.from_numpy(draw(layers[0])[0]).cuda()
+    wb = [tuple(torch.from_numpy(a).cuda() for a in draw(l)[1:]) for l in layers]
+    chain = mnn.ConvChain(layers, stream=stream)
+    for i, (w, b) in enumerate(wb):
+        chain.set_weights(i, w, b, stream=stream)
+    plans = [mnn.ConvPlan.for_layer(l, stream=stream) for l in layers]
+    outs = [torch.empty(l.out_shape, dtype=torch.float32, device="cuda") for l in layers]
+
+    def layerwise():
+        cur = x
+        for pl, (w, b), y in zip(plans, wb, outs):
+            pl.run(cur, w, b, y, stream=stream)
+            cur = y
+
+    y_chain = torch.empty(layers[-1].out_shape, dtype=torch.float32, device="cuda")
+    y_graph = chain.capture(x, torch.empty_like(y_chain))
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_layerwise = timed(layerwise)
+    ms_eager = timed(lambda: chain.run(x, y_chain, stream=stream))
+    ms_graph = timed(lambda: chain.replay(stream=stream))
+    same = bool(torch.equal(outs[-1], y_chain) and torch.equal(y_chain, y_graph))
+    info = chain.info
+    flops = sum(l.direct_flops for l in layers)
+    res = {"chain": kind, "batch": batch, "layers": [l.name for l in layers],
+           "schemes": [chain.describe(i) for i in range(len(layers))],
+           "ms_layer_by_layer": round(ms_layerwise, 5), "ms_chain_eager": round(ms_eager, 5),
+           "ms_chain_graph": round(ms_graph, 5), "graph_gflops_direct_count": round(flops / (ms_graph * 1e-3) / 1e9, 1),
+           "outputs_identical": same, "kernels_per_run": info["kernels_per_run"],
+           "arena_MB": round(info["arena_bytes"] / 1e6, 3), "unshared_MB": round(info["unshared_bytes"] / 1e6, 3),
+           "live_peak_MB": round(info["live_peak_bytes"] / 1e6, 3), "weights_MB": round(info["weight_bytes"] / 1e6, 3)}
+    chain.close()
+    for pl in plans:
+        pl.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -251,6 +302,9 @@ def main():
                            "layers": [{"layer": e["layer"], "scheme": e["scheme"], "ms": e["ms"], "stage_ms": e["stage_ms"],
                                        "stage_rate": e.get("stage_rate", {})} for e in r["per_layer"]]})
         out["other_workloads"] = others
+        # preparation-execution decoupling over a chain of layers (the launch-bound batch-1 regime and batch 32)
+        out["chained_execution"] = [run_chain("resnet18_trunk", b, 200 if b == 1 else 50, 10, stream, mnn, torch)
+                                    for b in (1, 32)]
     if args.plan_file:
         mnn.cache_save(args.plan_file)
     if args.calibrate_copy:

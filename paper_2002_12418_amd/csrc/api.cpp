@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <memory>
@@ -266,19 +267,28 @@ int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
     float best_ms = -1.f;
     const int iters = 4;
     int rc = MNN_OK;
+    const bool tune_log = std::getenv("MNNCONV_TUNE_LOG") != nullptr;    // one line per timed configuration on stderr
     for (int v = 1; v < gemm_variant_count(p.prec) && !rc; ++v) {
         p.variant = v;
         p.splitk = 1; p.splitk_partial = nullptr; p.splitk_counters = nullptr;
         float ms = -1.f;
         if ((rc = time_gemm(p, s, e0, e1, iters, &ms))) break;
         if (ms >= 0.f && (best_ms < 0.f || ms < best_ms)) { best_ms = ms; best = GemmChoice{v, 1}; }
+        if (tune_log && ms >= 0.f)
+            std::fprintf(stderr, "[mnnconv tune] M=%d cols=%d R=%d batch=%d gather=%d %s: %.2f us\n", p.M, p.Ncols, p.R, p.batch,
+                         p.gather, gemm_variant_name(p.prec, v), ms * 1e3f / iters);
         int bm = 0, bn = 0, bk = 0;
         if (ms < 0.f || !gemm_variant_tile(p.prec, v, &bm, &bn, &bk)) continue;
         const long long tiles = (long long)((p.M + bm - 1) / bm) * ((p.Ncols + bn - 1) / bn) * p.batch;
         const int chunks = (p.R + bk - 1) / bk;
-        for (int sk = 2; sk <= 32 && !rc; sk *= 2) {
-            if (tiles >= 384 || tiles * sk > 1024 || sk > chunks) break;
-            if ((long long)(sk - 1) * ((chunks + sk - 1) / sk) >= chunks) continue;     // an empty slice
+        // every split count whose slices are all non-empty and equally long up to the last one:
+        // sk = ceil(chunks / per) for per = chunks/2 ... 1 chunks per slice
+        int prev_sk = 1;
+        for (int per = chunks / 2; per >= 1 && !rc; --per) {
+            const int sk = (chunks + per - 1) / per;
+            if (sk == prev_sk) continue;
+            prev_sk = sk;
+            if (tiles >= 384 || tiles * sk > 1024 || sk > 64) break;
             long long pf = 0, cn = 0;
             gemm_splitk_workspace(p, bm, bn, sk, &pf, &cn);
             float* part = nullptr;
@@ -296,6 +306,8 @@ int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
             (void)hipFree(part);
             (void)hipFree(cnt);
             if (!rc && ms >= 0.f && ms < best_ms) { best_ms = ms; best = GemmChoice{v, sk}; }
+            if (tune_log && !rc && ms >= 0.f)
+                std::fprintf(stderr, "[mnnconv tune]     %s splitk=%d: %.2f us\n", gemm_variant_name(p.prec, v), sk, ms * 1e3f / iters);
         }
     }
     (void)hipEventDestroy(e0);
@@ -1187,7 +1199,7 @@ int mnn_conv_cache_load(const char* path)
                         if (std::fscanf(f, "%lld", &v[i]) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
                     int variant = 0, splitk = 1;
                     if (!rc && std::fscanf(f, " | %d %d", &variant, &splitk) != 2) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
-                    if (!rc && (splitk < 1 || splitk > 32)) rc = fail(MNN_E_INVALID_ARG, "bad split in %s", path);
+                    if (!rc && (splitk < 1 || splitk > 64)) rc = fail(MNN_E_INVALID_ARG, "bad split in %s", path);
                     const int vprec = v.empty() ? 0 : (int)v.back();
                     if (!rc && (vprec < 0 || vprec > MNN_GEMM_BF16X3 || variant < 0 || variant >= gemm_variant_count(vprec)))
                         rc = fail(MNN_E_INVALID_ARG, "unknown GEMM configuration %d in %s", variant, path);

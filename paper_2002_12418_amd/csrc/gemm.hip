@@ -41,9 +41,13 @@ __device__ __forceinline__ int xcd_remap(int bid, int total)
 
 // MODE 0: B read element by element through the (col / L, col % L) mapping; 1: the same with 16-byte
 // loads; 2: B gathered from an NCHW tensor (implicit GEMM of the sliding-window convolution).
-template <int BM, int BN, int BK, int WM, int WN, int MODE>
+// PF: how many chunks ahead of the one being multiplied the global loads run (register stages).  One is
+// enough when several workgroups share a CU; short grids (batch-1 layers) are bound by memory latency per
+// chunk and want their whole slice of the reduction in flight at once.
+template <int BM, int BN, int BK, int WM, int WN, int MODE, int PF = 1>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, int tilesM, int tilesN, int total)
 {
+    static_assert(PF == 1 || PF % 2 == 0, "the LDS buffer index is derived from the stage index");
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32;          // 32x32 tiles per wavefront along m
     constexpr int TN = BN / WN / 32;          // ... along columns
@@ -110,15 +114,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
         }
     }
 
-    float4 ra[LA], rb[LB];
-    auto load_global = [&](int r0) {
+    float4 ra[PF][LA], rb[PF][LB];
+    auto load_global = [&](int st, int r0) {
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
             const int r = r0 + a_row[j];
             if (a_ok[j] && r < p.R)
-                ra[j] = *reinterpret_cast<const float4*>(Ab + (long long)r * p.lda + m0 + a_col[j]);
+                ra[st][j] = *reinterpret_cast<const float4*>(Ab + (long long)r * p.lda + m0 + a_col[j]);
             else
-                ra[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                ra[st][j] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
         for (int j = 0; j < LB; ++j) {
@@ -136,28 +140,28 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
                     const bool ok = rok && b_ok[j][e] && iy >= 0 && iy < p.cv_H && ix >= 0 && ix < p.cv_W;
                     v[e] = ok ? plane[b_off[j][e] + (long long)iy * p.cv_W + ix] : 0.f;
                 }
-                rb[j] = make_float4(v[0], v[1], v[2], v[3]);
+                rb[st][j] = make_float4(v[0], v[1], v[2], v[3]);
                 continue;
             }
             const float* rowp = Bb + (long long)r * p.strideB_row;
             if constexpr (VEC) {
                 if (rok && b_ok[j][0])
-                    rb[j] = *reinterpret_cast<const float4*>(rowp + b_off[j][0]);
+                    rb[st][j] = *reinterpret_cast<const float4*>(rowp + b_off[j][0]);
                 else
-                    rb[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    rb[st][j] = make_float4(0.f, 0.f, 0.f, 0.f);
             } else {
                 float v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = (rok && b_ok[j][e]) ? rowp[b_off[j][e]] : 0.f;
-                rb[j] = make_float4(v[0], v[1], v[2], v[3]);
+                rb[st][j] = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
     };
-    auto store_lds = [&](int buf) {
+    auto store_lds = [&](int buf, int st) {
 #pragma unroll
-        for (int j = 0; j < LA; ++j) *reinterpret_cast<float4*>(&As[buf][a_row[j]][a_col[j]]) = ra[j];
+        for (int j = 0; j < LA; ++j) *reinterpret_cast<float4*>(&As[buf][a_row[j]][a_col[j]]) = ra[st][j];
 #pragma unroll
-        for (int j = 0; j < LB; ++j) *reinterpret_cast<float4*>(&Bs[buf][b_row[j]][b_col[j]]) = rb[j];
+        for (int j = 0; j < LB; ++j) *reinterpret_cast<float4*>(&Bs[buf][b_row[j]][b_col[j]]) = rb[st][j];
     };
 
     floatx16 acc[TM][TN];
@@ -172,8 +176,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     const int per_split = (all_chunks + splitk - 1) / splitk;
     const int ch0 = split * per_split;
     const int nchunks = (all_chunks - ch0 < per_split ? all_chunks - ch0 : per_split);   // launcher guarantees >= 1
-    load_global(ch0 * BK);
-    store_lds(0);
+    // register stage u holds chunk c (c % PF == u) until it has been copied to LDS buffer c % 2
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (u < nchunks) load_global(u, (ch0 + u) * BK);
+    store_lds(0, 0);
     __syncthreads();
 
     const int lrow = lane >> 5;               // which of the 2 reduction rows of an MFMA step
@@ -181,24 +188,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     const int am = wm * (BM / WM) + lcol;
     const int bn = wn * (BN / WN) + lcol;
 
-    for (int ch = 0; ch < nchunks; ++ch) {
-        const int buf = ch & 1;
-        if (ch + 1 < nchunks) load_global((ch0 + ch + 1) * BK);
+    for (int ch = 0; ch < nchunks; ch += PF) {
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            float av[TM], bv[TN];
+        for (int u = 0; u < PF; ++u) {
+            const int c = ch + u;
+            if (c >= nchunks) break;
+            const int buf = (PF == 1) ? (c & 1) : (u & 1);
+            if (c + PF < nchunks) load_global(u, (ch0 + c + PF) * BK);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) av[i] = As[buf][kk + lrow][am + i * 32];
+            for (int kk = 0; kk < BK; kk += 2) {
+                float av[TM], bv[TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][kk + lrow][bn + j * 32];
+                for (int i = 0; i < TM; ++i) av[i] = As[buf][kk + lrow][am + i * 32];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][kk + lrow][bn + j * 32];
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+            }
+            if (c + 1 < nchunks) store_lds(buf ^ 1, (u + 1) % PF);
+            __syncthreads();
         }
-        if (ch + 1 < nchunks) store_lds(buf ^ 1);
-        __syncthreads();
     }
 
     if (splitk > 1) {
@@ -227,7 +239,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN, int PF = 1>
 hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
 {
     const int tilesM = (p.M + BM - 1) / BM;
@@ -243,13 +255,13 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
             return hipErrorInvalidValue;
     }
     if (p.gather)
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2, PF>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
                            0, s, p, tilesM, tilesN, (int)total);
     else if (vec)
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1, PF>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
                            0, s, p, tilesM, tilesN, (int)total);
     else
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0, PF>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
                            0, s, p, tilesM, tilesN, (int)total);
     return hipGetLastError();
 }
@@ -273,6 +285,11 @@ const Variant kVariants[] = {
     {"128x128x16_w4x2", launch_cfg<128, 128, 16, 4, 2>, 128, 128, 16},
     {"64x128x32_w1x4", launch_cfg<64, 128, 32, 1, 4>, 64, 128, 32},
     {"64x256x16_w1x4", launch_cfg<64, 256, 16, 1, 4>, 64, 256, 16},
+    // deeper global-load pipelines for grids too short to hide memory latency by occupancy
+    {"64x64x32_w2x2_pf2", launch_cfg<64, 64, 32, 2, 2, 2>, 64, 64, 32},
+    {"64x64x32_w2x2_pf4", launch_cfg<64, 64, 32, 2, 2, 4>, 64, 64, 32},
+    {"64x64x16_w2x2_pf4", launch_cfg<64, 64, 16, 2, 2, 4>, 64, 64, 16},
+    {"128x64x32_w2x2_pf2", launch_cfg<128, 64, 32, 2, 2, 2>, 128, 64, 32},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 }  // namespace

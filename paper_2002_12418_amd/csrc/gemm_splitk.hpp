@@ -33,17 +33,38 @@ __device__ __forceinline__ bool splitk_combine(splitk_floatx16 (&acc)[TM][TN], f
     if (arrived != (unsigned)(splitk - 1)) return false;
     __threadfence();
     const float* base = partial + (long long)tile * splitk * REGS * NT + tid;
+    // Slice by slice, so that every element is summed in slice order whoever arrived when; the 16 loads of
+    // a slice (and of the next three) are independent and in flight together.
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j) {
+            const float* blk = base + (long long)((i * TN + j) * 16) * NT;
+            splitk_floatx16 s;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float s = 0.f;
-                for (int sl = 0; sl < splitk; ++sl)
-                    s += __builtin_nontemporal_load(base + ((long long)sl * REGS + (i * TN + j) * 16 + r) * NT);
-                acc[i][j][r] = s;
+            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+            int sl = 0;
+            for (; sl + 4 <= splitk; sl += 4) {
+                float v[4][16];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        v[q][r] = __builtin_nontemporal_load(blk + ((long long)(sl + q) * REGS + r) * NT);
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[r] += v[q][r];
             }
+            for (; sl < splitk; ++sl) {
+                float v[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[r] = __builtin_nontemporal_load(blk + ((long long)sl * REGS + r) * NT);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] += v[r];
+            }
+            acc[i][j] = s;
+        }
     if (tid == 0) counters[tile] = 0u;             // ready for the next launch
     return true;
 }
