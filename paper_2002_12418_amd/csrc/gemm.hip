@@ -29,6 +29,7 @@ namespace mnnconv {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 
 constexpr int kXcds = 8;
 
@@ -44,8 +45,15 @@ __device__ __forceinline__ int xcd_remap(int bid, int total)
 // PF: how many chunks ahead of the one being multiplied the global loads run (register stages).  One is
 // enough when several workgroups share a CU; short grids (batch-1 layers) are bound by memory latency per
 // chunk and want their whole slice of the reduction in flight at once.
-template <int BM, int BN, int BK, int WM, int WN, int MODE, int PF = 1>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, int tilesM, int tilesN, int total)
+//
+// BUF: operands are read through buffer descriptors with 32-bit byte offsets; the hardware range check
+// returns zero for an offset outside the operand, so ragged edges cost neither a branch nor a select and
+// the compiler can count exactly how many loads are in flight (a branch around a load forces it to wait
+// for all of them).  Needs every operand of one batch to span less than 2 GiB; larger ones take the
+// pointer-based loader (BUF = false).
+template <int BM, int BN, int BK, int WM, int WN, int MODE, int PF = 1, bool BUF = true>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, int tilesM, int tilesN, int total,
+                                                                unsigned a_bytes, unsigned b_bytes)
 {
     static_assert(PF == 1 || PF % 2 == 0, "the LDS buffer index is derived from the stage index");
     constexpr int NT = WM * WN * 64;
@@ -80,42 +88,135 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     const float* __restrict__ Bb = p.B + (long long)b * p.strideB_batch;
 
     // ---- per-thread load slots (fixed over the K loop except for the row)
+    constexpr bool VEC = (MODE == 1);
+    constexpr int NE = VEC ? 1 : 4;           // loads per B slot
+    constexpr unsigned kOutside = 0x80000000u;   // offset no operand reaches (all are < 2 GiB): reads as zero
     int a_row[LA], a_col[LA];
-    bool a_ok[LA];
+    int b_row[LB], b_col[LB];
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
         const int s = tid + j * NT;
         a_row[j] = s / (BM / 4);
         a_col[j] = (s % (BM / 4)) * 4;
-        a_ok[j] = (m0 + a_col[j]) < p.lda;
     }
-    constexpr bool VEC = (MODE == 1);
-    int b_row[LB], b_col[LB];
-    long long b_off[LB][VEC ? 1 : 4];
-    bool b_ok[LB][VEC ? 1 : 4];
-    int g_y[LB][MODE == 2 ? 4 : 1], g_x[LB][MODE == 2 ? 4 : 1];   // gather: top-left input coordinate of the column
 #pragma unroll
     for (int j = 0; j < LB; ++j) {
         const int s = tid + j * NT;
         b_row[j] = s / (BN / 4);
         b_col[j] = (s % (BN / 4)) * 4;
+    }
+    // gather (MODE 2): reduction row r = (c * kh + dy) * kw + dx is kept per slot as (c, dy, dx) and advanced
+    // by BK rows per chunk without dividing; columns keep their image offset and top-left input coordinate
+    int g_c[LB], g_dy[LB], g_dx[LB];
+    int step_c = 0, step_dy = 0, step_dx = 0;
+    int g_off[LB][MODE == 2 ? 4 : 1], g_y[LB][MODE == 2 ? 4 : 1], g_x[LB][MODE == 2 ? 4 : 1];
+    bool b_ok[LB][NE];
+    if constexpr (MODE == 2) {
 #pragma unroll
-        for (int e = 0; e < (VEC ? 1 : 4); ++e) {
-            const int col = n0 + b_col[j] + e;
-            b_ok[j][e] = col < p.Ncols;
-            const int img = col / p.L, rest = col % p.L;
-            if constexpr (MODE == 2) {
-                b_off[j][e] = (long long)img * p.cv_C * p.cv_H * p.cv_W;
+        for (int j = 0; j < LB; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int col = n0 + b_col[j] + e;
+                b_ok[j][e] = col < p.Ncols;
+                const int img = col / p.L, rest = col % p.L;
+                g_off[j][e] = img * p.cv_C * p.cv_H * p.cv_W;      // the launcher checked: fewer than 2^31 elements
                 g_y[j][e] = (rest / p.cv_Wo) * p.cv_sh - p.cv_ph;
                 g_x[j][e] = (rest % p.cv_Wo) * p.cv_sw - p.cv_pw;
-            } else {
-                b_off[j][e] = (long long)img * p.strideB_img + rest;
             }
-        }
     }
+    auto gather_advance = [&](int j) {
+        g_c[j] += step_c;
+        g_dy[j] += step_dy;
+        g_dx[j] += step_dx;
+        if (g_dx[j] >= p.cv_kw) { g_dx[j] -= p.cv_kw; g_dy[j] += 1; }
+        if (g_dy[j] >= p.cv_kh) { g_dy[j] -= p.cv_kh; g_c[j] += 1; }
+    };
 
     float4 ra[PF][LA], rb[PF][LB];
-    auto load_global = [&](int st, int r0) {
+
+    // -- loader through buffer descriptors
+    unsigned a_base[LA], b_base[LB][NE];       // byte offset of the slot in row 0, or kOutside
+    __amdgpu_buffer_rsrc_t rsA, rsB;
+    if constexpr (BUF) {
+        rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Ab), 0, (int)a_bytes, 0x00020000);
+        rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Bb), 0, (int)b_bytes, 0x00020000);
+#pragma unroll
+        for (int j = 0; j < LA; ++j)
+            a_base[j] = (m0 + a_col[j]) < p.lda ? (unsigned)(m0 + a_col[j]) * 4u : kOutside;
+        if constexpr (MODE != 2) {
+#pragma unroll
+            for (int j = 0; j < LB; ++j)
+#pragma unroll
+                for (int e = 0; e < NE; ++e) {
+                    const int col = n0 + b_col[j] + e;
+                    const int img = col / p.L, rest = col % p.L;
+                    b_base[j][e] = col < p.Ncols ? (unsigned)(img * (int)p.strideB_img + rest) * 4u : kOutside;
+                }
+        }
+    }
+    auto load_buf = [&](int st, int r0) {
+        // A: rows past R lie behind the end of the descriptor and read as zero by themselves
+#pragma unroll
+        for (int j = 0; j < LA; ++j) {
+            const unsigned off = a_base[j] + (unsigned)(r0 + a_row[j]) * (unsigned)p.lda * 4u;
+            const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(rsA, (int)off, 0, 0);
+            ra[st][j] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+        }
+#pragma unroll
+        for (int j = 0; j < LB; ++j) {
+            if constexpr (MODE == 2) {
+                const int c = g_c[j];
+                const int dy = g_dy[j] * p.cv_dh, dx = g_dx[j] * p.cv_dw;
+                const bool cok = c < p.cv_C;                       // same as r < R
+                const int coff = c * p.cv_H * p.cv_W;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int iy = g_y[j][e] + dy, ix = g_x[j][e] + dx;
+                    const bool ok = cok && b_ok[j][e] && (unsigned)iy < (unsigned)p.cv_H && (unsigned)ix < (unsigned)p.cv_W;
+                    const unsigned off = ok ? (unsigned)(g_off[j][e] + coff + iy * p.cv_W + ix) * 4u : kOutside;
+                    v[e] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsB, (int)off, 0, 0));
+                }
+                rb[st][j] = make_float4(v[0], v[1], v[2], v[3]);
+                gather_advance(j);
+            } else {
+                // B: a row past R may lie inside the operand (next image / next plane), so it is masked
+                const int r = r0 + b_row[j];
+                const unsigned roff = r < p.R ? (unsigned)r * (unsigned)p.strideB_row * 4u : kOutside;
+                if constexpr (VEC) {
+                    const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(rsB, (int)(b_base[j][0] | roff) < 0 ? (int)kOutside : (int)(b_base[j][0] + roff), 0, 0);
+                    rb[st][j] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+                } else {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const unsigned off = (int)(b_base[j][e] | roff) < 0 ? kOutside : b_base[j][e] + roff;
+                        v[e] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsB, (int)off, 0, 0));
+                    }
+                    rb[st][j] = make_float4(v[0], v[1], v[2], v[3]);
+                }
+            }
+        }
+    };
+
+    // -- loader through 64-bit addresses (operands of 2 GiB and more)
+    bool a_ok[LA];
+    long long b_off[LB][NE];
+    if constexpr (!BUF) {
+#pragma unroll
+        for (int j = 0; j < LA; ++j) a_ok[j] = (m0 + a_col[j]) < p.lda;
+        if constexpr (MODE != 2) {
+#pragma unroll
+            for (int j = 0; j < LB; ++j)
+#pragma unroll
+                for (int e = 0; e < NE; ++e) {
+                    const int col = n0 + b_col[j] + e;
+                    b_ok[j][e] = col < p.Ncols;
+                    b_off[j][e] = (long long)(col / p.L) * p.strideB_img + col % p.L;
+                }
+        }
+    }
+    auto load_ptr = [&](int st, int r0) {
 #pragma unroll
         for (int j = 0; j < LA; ++j) {
             const int r = r0 + a_row[j];
@@ -129,18 +230,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
             const int r = r0 + b_row[j];
             const bool rok = r < p.R;
             if constexpr (MODE == 2) {
-                const int taps = p.cv_kh * p.cv_kw;
-                const int c = r / taps, rem = r % taps;
-                const int dy = (rem / p.cv_kw) * p.cv_dh, dx = (rem % p.cv_kw) * p.cv_dw;
+                const int c = g_c[j];
+                const int dy = g_dy[j] * p.cv_dh, dx = g_dx[j] * p.cv_dw;
                 const float* plane = Bb + (long long)c * p.cv_H * p.cv_W;
                 float v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int iy = g_y[j][e] + dy, ix = g_x[j][e] + dx;
-                    const bool ok = rok && b_ok[j][e] && iy >= 0 && iy < p.cv_H && ix >= 0 && ix < p.cv_W;
-                    v[e] = ok ? plane[b_off[j][e] + (long long)iy * p.cv_W + ix] : 0.f;
+                    const bool ok = rok && b_ok[j][e] && (unsigned)iy < (unsigned)p.cv_H && (unsigned)ix < (unsigned)p.cv_W;
+                    v[e] = ok ? plane[(long long)g_off[j][e] + (long long)iy * p.cv_W + ix] : 0.f;
                 }
                 rb[st][j] = make_float4(v[0], v[1], v[2], v[3]);
+                gather_advance(j);
                 continue;
             }
             const float* rowp = Bb + (long long)r * p.strideB_row;
@@ -156,6 +257,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
                 rb[st][j] = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
+    };
+    auto load_global = [&](int st, int r0) {
+        if constexpr (BUF) load_buf(st, r0);
+        else load_ptr(st, r0);
     };
     auto store_lds = [&](int buf, int st) {
 #pragma unroll
@@ -176,7 +281,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     const int per_split = (all_chunks + splitk - 1) / splitk;
     const int ch0 = split * per_split;
     const int nchunks = (all_chunks - ch0 < per_split ? all_chunks - ch0 : per_split);   // launcher guarantees >= 1
-    // register stage u holds chunk c (c % PF == u) until it has been copied to LDS buffer c % 2
+    if constexpr (MODE == 2) {
+        const int taps = p.cv_kh * p.cv_kw;
+        step_c = BK / taps;
+        step_dy = (BK % taps) / p.cv_kw;
+        step_dx = (BK % taps) % p.cv_kw;
+#pragma unroll
+        for (int j = 0; j < LB; ++j) {
+            const int r = ch0 * BK + b_row[j];
+            const int rem = r % taps;
+            g_c[j] = r / taps;
+            g_dy[j] = rem / p.cv_kw;
+            g_dx[j] = rem % p.cv_kw;
+        }
+    }
+    // register stage u holds chunk c (c % PF == u) until it has been copied to LDS buffer c % 2;
+    // load_global is called once per chunk, in chunk order (the gather state advances with each call)
 #pragma unroll
     for (int u = 0; u < PF; ++u)
         if (u < nchunks) load_global(u, (ch0 + u) * BK);
@@ -195,18 +315,26 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
             if (c >= nchunks) break;
             const int buf = (PF == 1) ? (c & 1) : (u & 1);
             if (c + PF < nchunks) load_global(u, (ch0 + c + PF) * BK);
+            // operands of step kk + 2 are read from LDS while the MFMAs of step kk run
+            float av[2][TM], bv[2][TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) av[0][i] = As[buf][lrow][am + i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bv[0][j] = Bs[buf][lrow][bn + j * 32];
 #pragma unroll
             for (int kk = 0; kk < BK; kk += 2) {
-                float av[TM], bv[TN];
+                const int cur = (kk >> 1) & 1, nxt = cur ^ 1;
+                if (kk + 2 < BK) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i) av[i] = As[buf][kk + lrow][am + i * 32];
+                    for (int i = 0; i < TM; ++i) av[nxt][i] = As[buf][kk + 2 + lrow][am + i * 32];
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][kk + lrow][bn + j * 32];
+                    for (int j = 0; j < TN; ++j) bv[nxt][j] = Bs[buf][kk + 2 + lrow][bn + j * 32];
+                }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bv[cur][j], acc[i][j], 0, 0, 0);
             }
             if (c + 1 < nchunks) store_lds(buf ^ 1, (u + 1) % PF);
             __syncthreads();
@@ -239,7 +367,25 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int PF = 1>
+// Bytes one batch of each operand spans, and whether the descriptor-based loader can address them.
+struct Extents { unsigned a_bytes, b_bytes; bool narrow; };
+Extents operand_extents(const GemmProblem& p)
+{
+    const long long a = (long long)p.R * p.lda * 4;
+    long long b;
+    const long long imgs = (p.Ncols + p.L - 1) / p.L;
+    if (p.gather) b = imgs * p.cv_C * p.cv_H * p.cv_W * 4;
+    else b = ((imgs - 1) * p.strideB_img + (long long)(p.R - 1) * p.strideB_row + p.L) * 4;
+    Extents e;
+    // offsets run a few chunks past the last row before the range check stops them: keep them below 2^31
+    e.narrow = a > 0 && b > 0 && a < (1ll << 30) && b < (1ll << 31) - 64 && (long long)p.lda * 4 * 1024 < (1ll << 30) &&
+               p.strideB_img >= 0 && p.strideB_row >= 0;
+    e.a_bytes = e.narrow ? (unsigned)a : 0u;
+    e.b_bytes = e.narrow ? (unsigned)b : 0u;
+    return e;
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int PF = 1, bool BUF = true>
 hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
 {
     const int tilesM = (p.M + BM - 1) / BM;
@@ -254,15 +400,18 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
         if ((long long)(splitk - 1) * per_split >= all_chunks || !p.splitk_partial || !p.splitk_counters || total * splitk >= (1ll << 31))
             return hipErrorInvalidValue;
     }
+    const Extents ex = operand_extents(p);
+    if (BUF && !ex.narrow) return hipErrorNotSupported;       // the caller falls back to the 64-bit loader
+    const dim3 grid((unsigned)(total * splitk)), block(WM * WN * 64);
     if (p.gather)
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2, PF>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
-                           0, s, p, tilesM, tilesN, (int)total);
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
+                           (int)total, ex.a_bytes, ex.b_bytes);
     else if (vec)
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1, PF>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
-                           0, s, p, tilesM, tilesN, (int)total);
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
+                           (int)total, ex.a_bytes, ex.b_bytes);
     else
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0, PF>), dim3((unsigned)(total * splitk)), dim3(WM * WN * 64),
-                           0, s, p, tilesM, tilesN, (int)total);
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
+                           (int)total, ex.a_bytes, ex.b_bytes);
     return hipGetLastError();
 }
 
@@ -343,7 +492,11 @@ hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s)
                      (p.strideB_img % 4 == 0) && (p.strideB_row % 4 == 0);
     int v = p.variant;
     if (v == 0) v = (p.M <= 64) ? 2 : 1;
-    return kVariants[v].fn(p, vec, s);
+    const hipError_t e = kVariants[v].fn(p, vec, s);
+    if (e != hipErrorNotSupported) return e;
+    // an operand of 2 GiB or more per batch: one tile configuration with 64-bit addressing serves all variants
+    if (p.splitk > 1) return hipErrorInvalidValue;              // split-K scratch was sized for another tile
+    return launch_cfg<128, 128, 16, 2, 2, 1, false>(p, vec, s);
 }
 
 }  // namespace mnnconv
