@@ -439,6 +439,10 @@ const Variant kVariants[] = {
     {"64x64x32_w2x2_pf4", launch_cfg<64, 64, 32, 2, 2, 4>, 64, 64, 32},
     {"64x64x16_w2x2_pf4", launch_cfg<64, 64, 16, 2, 2, 4>, 64, 64, 16},
     {"128x64x32_w2x2_pf2", launch_cfg<128, 64, 32, 2, 2, 2>, 128, 64, 32},
+    {"128x128x16_w4x2_pf2", launch_cfg<128, 128, 16, 4, 2, 2>, 128, 128, 16},
+    {"128x128x16_w2x2_pf2", launch_cfg<128, 128, 16, 2, 2, 2>, 128, 128, 16},
+    {"256x128x16_w4x2_pf2", launch_cfg<256, 128, 16, 4, 2, 2>, 256, 128, 16},
+    {"128x128x32_w4x2_pf2", launch_cfg<128, 128, 32, 4, 2, 2>, 128, 128, 32},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 }  // namespace
