@@ -53,7 +53,7 @@ __device__ __forceinline__ int xcd_remap(int bid, int total)
 // pointer-based loader (BUF = false).
 template <int BM, int BN, int BK, int WM, int WN, int MODE, int PF = 1, bool BUF = true>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, int tilesM, int tilesN, int total,
-                                                                unsigned a_bytes, unsigned b_bytes)
+                                                                unsigned a_bytes, unsigned b_bytes, int vecD)
 {
     static_assert(PF == 1 || PF % 2 == 0, "the LDS buffer index is derived from the stage index");
     constexpr int NT = WM * WN * 64;
@@ -66,8 +66,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     static_assert(A4 % NT == 0 && B4 % NT == 0, "tile must divide evenly over the workgroup");
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 2 == 0, "tile shape");
 
-    __shared__ __attribute__((aligned(16))) float As[2][BK][BM];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN];
+    // one LDS block: the operand double buffer during the reduction, per-wavefront 32x32 staging tiles
+    // (row stride CS) for the vectorised result stores afterwards
+    constexpr int CS = 36;
+    constexpr int AB_FLOATS = 2 * BK * (BM + BN);
+    constexpr int C_FLOATS = (NT / 64) * 32 * CS;
+    __shared__ __attribute__((aligned(16))) float smem[AB_FLOATS > C_FLOATS ? AB_FLOATS : C_FLOATS];
+    float (*As)[BK][BM] = reinterpret_cast<float (*)[BK][BM]>(smem);
+    float (*Bs)[BK][BN] = reinterpret_cast<float (*)[BK][BN]>(smem + 2 * BK * BM);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -346,6 +352,39 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     }
     // ---- epilogue: lane holds column lcol of each tile, rows 8*(r/4) + 4*(lane/32) + r%4
     float* __restrict__ Db = p.D + (long long)b * p.strideD_batch;
+    if (vecD) {
+        // Through LDS, so that a lane stores 4 consecutive columns of one row (16 bytes) and a store
+        // instruction covers 8 rows x 128 bytes, instead of 2 rows x 128 bytes in 4-byte pieces.  The
+        // staging tile is private to the wavefront: its LDS accesses execute in order, no barrier needed
+        // (the reduction loop ended with one, so the operand buffers are free).
+        float* cw = smem + wave * 32 * CS;
+        const int rrow = lane >> 3, rc4 = (lane & 7) * 4;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * (BN / WN) + j * 32 + rc4;
+            const bool cok = col < p.Ncols;                   // Ncols % 4 == 0: all four columns or none
+            const long long coff = (long long)(col / p.L) * p.strideD_img + (col % p.L);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) cw[(8 * (r / 4) + 4 * lrow + (r % 4)) * CS + lcol] = acc[i][j][r];
+#pragma unroll
+                for (int ps = 0; ps < 4; ++ps) {
+                    const int row = ps * 8 + rrow;
+                    const int m = m0 + wm * (BM / WM) + i * 32 + row;
+                    float4 v = *reinterpret_cast<const float4*>(&cw[row * CS + rc4]);
+                    if (cok && m < p.M) {
+                        if (p.bias) {
+                            const float bv = p.bias[m];
+                            v.x += bv; v.y += bv; v.z += bv; v.w += bv;
+                        }
+                        *reinterpret_cast<float4*>(Db + coff + (long long)m * p.strideD_row) = v;
+                    }
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int col = n0 + wn * (BN / WN) + j * 32 + lcol;
@@ -403,15 +442,17 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
     const Extents ex = operand_extents(p);
     if (BUF && !ex.narrow) return hipErrorNotSupported;       // the caller falls back to the 64-bit loader
     const dim3 grid((unsigned)(total * splitk)), block(WM * WN * 64);
+    const int vecD = ((reinterpret_cast<uintptr_t>(p.D) & 15u) == 0 && p.L % 4 == 0 && p.Ncols % 4 == 0 && p.strideD_batch % 4 == 0 &&
+                      p.strideD_img % 4 == 0 && p.strideD_row % 4 == 0) ? 1 : 0;
     if (p.gather)
         hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
-                           (int)total, ex.a_bytes, ex.b_bytes);
+                           (int)total, ex.a_bytes, ex.b_bytes, vecD);
     else if (vec)
         hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
-                           (int)total, ex.a_bytes, ex.b_bytes);
+                           (int)total, ex.a_bytes, ex.b_bytes, vecD);
     else
         hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
-                           (int)total, ex.a_bytes, ex.b_bytes);
+                           (int)total, ex.a_bytes, ex.b_bytes, vecD);
     return hipGetLastError();
 }
 
