@@ -287,7 +287,7 @@ typedef struct {
     uint64_t arena_bytes;        /* the one allocation: activations + workspaces with reuse */
     uint64_t unshared_bytes;     /* the same buffers without reuse (sum of their sizes) */
     uint64_t live_peak_bytes;    /* most bytes alive at any layer: lower bound for arena_bytes */
-    uint64_t weight_bytes;       /* prepared weights, bias copies, split-K counters */
+    uint64_t weight_bytes;       /* prepared weights and bias copies */
 } mnn_chain_info_t;
 
 int mnn_chain_create(const mnn_chain_layer* layers, int32_t n_layers, const mnn_conv_options* options,

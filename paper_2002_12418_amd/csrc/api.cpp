@@ -270,7 +270,7 @@ int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
     const bool tune_log = std::getenv("MNNCONV_TUNE_LOG") != nullptr;    // one line per timed configuration on stderr
     for (int v = 1; v < gemm_variant_count(p.prec) && !rc; ++v) {
         p.variant = v;
-        p.splitk = 1; p.splitk_partial = nullptr; p.splitk_counters = nullptr;
+        p.splitk = 1; p.splitk_partial = nullptr;
         float ms = -1.f;
         if ((rc = time_gemm(p, s, e0, e1, iters, &ms))) break;
         if (ms >= 0.f && (best_ms < 0.f || ms < best_ms)) { best_ms = ms; best = GemmChoice{v, 1}; }
@@ -288,23 +288,16 @@ int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
             const int sk = (chunks + per - 1) / per;
             if (sk == prev_sk) continue;
             prev_sk = sk;
-            if (tiles >= 384 || tiles * sk > 1024 || sk > 64) break;
-            long long pf = 0, cn = 0;
-            gemm_splitk_workspace(p, bm, bn, sk, &pf, &cn);
+            if (tiles >= 512 || tiles * sk > 2048 || sk > 64) break;
+            const long long pf = gemm_splitk_workspace(p, sk);
             float* part = nullptr;
-            unsigned* cnt = nullptr;
-            if ((e = hipMalloc((void**)&part, (size_t)pf * sizeof(float))) != hipSuccess ||
-                (e = hipMalloc((void**)&cnt, (size_t)cn * sizeof(unsigned))) != hipSuccess ||
-                (e = hipMemset(cnt, 0, (size_t)cn * sizeof(unsigned))) != hipSuccess) {
-                if (part) (void)hipFree(part);
-                if (cnt) (void)hipFree(cnt);
+            if ((e = hipMalloc((void**)&part, (size_t)pf * sizeof(float))) != hipSuccess) {
                 rc = fail_hip(e, "hipMalloc split-K scratch");
                 break;
             }
-            p.splitk = sk; p.splitk_partial = part; p.splitk_counters = cnt;
+            p.splitk = sk; p.splitk_partial = part;
             rc = time_gemm(p, s, e0, e1, iters, &ms);
             (void)hipFree(part);
-            (void)hipFree(cnt);
             if (!rc && ms >= 0.f && ms < best_ms) { best_ms = ms; best = GemmChoice{v, sk}; }
             if (tune_log && !rc && ms >= 0.f)
                 std::fprintf(stderr, "[mnnconv tune]     %s splitk=%d: %.2f us\n", gemm_variant_name(p.prec, v), sk, ms * 1e3f / iters);
@@ -332,7 +325,6 @@ struct Impl {
     int gemm_variant = 0;      // tile configuration of the GEMM stage (0 = shape heuristic)
     int gemm_splitk = 1;       // workgroups per tile along the reduction
     float* sk_partial = nullptr; size_t sk_partial_bytes = 0;
-    unsigned* sk_counters = nullptr; size_t sk_counters_bytes = 0;
     // V, M and the split-K partials hold nothing between two runs.  A plan on its own allocates them;
     // a chain of layers binds them to a region of its arena instead (bind_transient).
     bool transient_external = false;
@@ -350,11 +342,9 @@ struct Impl {
             if (M) (void)hipFree(M);
             if (sk_partial) (void)hipFree(sk_partial);
         }
-        if (sk_counters) (void)hipFree(sk_counters);
         U = V = M = nullptr;
         sk_partial = nullptr;
-        sk_counters = nullptr;
-        U_bytes = V_bytes = M_bytes = sk_partial_bytes = sk_counters_bytes = 0;
+        U_bytes = V_bytes = M_bytes = sk_partial_bytes = 0;
     }
 
     int alloc_zero(float** p, size_t bytes, const char* what)
@@ -472,7 +462,6 @@ struct Impl {
         p->prec = scheme.prec;
         p->splitk = gemm_splitk;
         p->splitk_partial = sk_partial;
-        p->splitk_counters = sk_counters;
     }
 
     GemmProblem pointwise_gemm_problem(const float* x, const float* b, float* y) const
@@ -516,16 +505,8 @@ struct Impl {
         if (gemm_splitk == 1) return MNN_OK;
         int bm = 0, bn = 0, bk = 0;
         if (!gemm_variant_tile(p.prec, gemm_variant, &bm, &bn, &bk)) { gemm_splitk = 1; return MNN_OK; }
-        long long pf = 0, cn = 0;
-        gemm_splitk_workspace(p, bm, bn, gemm_splitk, &pf, &cn);
-        sk_partial_bytes = (size_t)pf * sizeof(float);
-        sk_counters_bytes = (size_t)cn * sizeof(unsigned);
-        int rc = alloc_transient(&sk_partial, sk_partial_bytes, "hipMalloc split-K partials");
-        if (rc) return rc;
-        float* c32 = nullptr;
-        rc = alloc_zero(&c32, sk_counters_bytes, "hipMalloc split-K counters");
-        sk_counters = reinterpret_cast<unsigned*>(c32);
-        return rc;
+        sk_partial_bytes = (size_t)gemm_splitk_workspace(p, gemm_splitk) * sizeof(float);
+        return alloc_transient(&sk_partial, sk_partial_bytes, "hipMalloc split-K partials");
     }
 
     int tune(hipStream_t s)
@@ -615,7 +596,7 @@ struct Impl {
         return MNN_OK;
     }
 
-    size_t bytes() const { return U_bytes + V_bytes + M_bytes + sk_partial_bytes + sk_counters_bytes; }
+    size_t bytes() const { return U_bytes + V_bytes + M_bytes + sk_partial_bytes; }
 };
 
 void describe_impl(const Impl& im, char* buf, size_t cap)
@@ -694,7 +675,8 @@ struct mnn_chain_s {
     {
         int k = 0;
         for (const auto& im : impls)
-            for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st) k += im->has_stage(st) ? 1 : 0;
+            for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st)
+                if (im->has_stage(st)) k += (st == MNN_STAGE_GEMM && im->gemm_splitk > 1) ? 2 : 1;   // + the slice reduction
         return k;
     }
 
@@ -1272,7 +1254,7 @@ int chain_create_impl(const mnn_chain_layer* layers, int32_t n_layers, const mnn
         if ((rc = im.tune((hipStream_t)stream))) return rc;
         const size_t bb = (size_t)ch->layers[i].s.c_out * sizeof(float);
         if ((e = hipMalloc((void**)&ch->bias[i], bb)) != hipSuccess) return fail_hip(e, "hipMalloc bias");
-        ch->weight_bytes += im.U_bytes + im.sk_counters_bytes + bb;
+        ch->weight_bytes += im.U_bytes + bb;
     }
     // the virtual walk: activation i lives over layers i and i+1, workspace i over layer i
     std::vector<ArenaBuffer> bufs;

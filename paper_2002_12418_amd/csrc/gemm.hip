@@ -23,7 +23,7 @@
 // then hit the same L2.
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
-#include "gemm_splitk.hpp"
+#include "gemm_epilogue.hpp"
 
 namespace mnnconv {
 namespace {
@@ -53,7 +53,7 @@ __device__ __forceinline__ int xcd_remap(int bid, int total)
 // pointer-based loader (BUF = false).
 template <int BM, int BN, int BK, int WM, int WN, int MODE, int PF = 1, bool BUF = true>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, int tilesM, int tilesN, int total,
-                                                                unsigned a_bytes, unsigned b_bytes, int vecD)
+                                                                unsigned a_bytes, unsigned b_bytes, int vecD, int ldc)
 {
     static_assert(PF == 1 || PF % 2 == 0, "the LDS buffer index is derived from the stage index");
     constexpr int NT = WM * WN * 64;
@@ -68,9 +68,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
 
     // one LDS block: the operand double buffer during the reduction, per-wavefront 32x32 staging tiles
     // (row stride CS) for the vectorised result stores afterwards
-    constexpr int CS = 36;
     constexpr int AB_FLOATS = 2 * BK * (BM + BN);
-    constexpr int C_FLOATS = (NT / 64) * 32 * CS;
+    constexpr int C_FLOATS = (NT / 64) * kStageFloats;
     __shared__ __attribute__((aligned(16))) float smem[AB_FLOATS > C_FLOATS ? AB_FLOATS : C_FLOATS];
     float (*As)[BK][BM] = reinterpret_cast<float (*)[BK][BM]>(smem);
     float (*Bs)[BK][BN] = reinterpret_cast<float (*)[BK][BN]>(smem + 2 * BK * BM);
@@ -347,61 +346,50 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
         }
     }
 
-    if (splitk > 1) {
-        if (!splitk_combine<TM, TN, NT>(acc, p.splitk_partial, p.splitk_counters, logical, split, splitk, tid)) return;
+    // ---- results (or this slice's partial results) to memory
+    const TileDest dest = tile_dest(p, b, split, splitk, ldc);
+    store_tiles<TM, TN>(acc, dest, p.M, p.Ncols, m0 + wm * (BM / WM), n0 + wn * (BN / WN), lane,
+                        smem + wave * kStageFloats, vecD);
+}
+
+// Adds the split-K slices P[split][batch][M][ldc] in slice order, applies the bias and writes D.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmProblem p, int ldc, int vecD)
+{
+    const int q = ldc >> 2;
+    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long rows = (long long)p.batch * p.M;
+    if (idx >= rows * q) return;
+    const int c4 = (int)(idx % q) * 4;
+    const long long bm = idx / q;
+    const int m = (int)(bm % p.M), b = (int)(bm / p.M);
+    const float* src = p.splitk_partial + bm * ldc + c4;
+    const long long slice = rows * ldc;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    int sl = 0;
+    for (; sl + 4 <= p.splitk; sl += 4) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(src + (long long)(sl + u) * slice);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
     }
-    // ---- epilogue: lane holds column lcol of each tile, rows 8*(r/4) + 4*(lane/32) + r%4
-    float* __restrict__ Db = p.D + (long long)b * p.strideD_batch;
+    for (; sl < p.splitk; ++sl) {
+        const float4 v = *reinterpret_cast<const float4*>(src + (long long)sl * slice);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    if (p.bias) {
+        const float bv = p.bias[m];
+        s.x += bv; s.y += bv; s.z += bv; s.w += bv;
+    }
+    float* Db = p.D + (long long)b * p.strideD_batch + (long long)m * p.strideD_row;
     if (vecD) {
-        // Through LDS, so that a lane stores 4 consecutive columns of one row (16 bytes) and a store
-        // instruction covers 8 rows x 128 bytes, instead of 2 rows x 128 bytes in 4-byte pieces.  The
-        // staging tile is private to the wavefront: its LDS accesses execute in order, no barrier needed
-        // (the reduction loop ended with one, so the operand buffers are free).
-        float* cw = smem + wave * 32 * CS;
-        const int rrow = lane >> 3, rc4 = (lane & 7) * 4;
+        *reinterpret_cast<float4*>(Db + (long long)(c4 / p.L) * p.strideD_img + (c4 % p.L)) = s;
+    } else {
+        const float o[4] = {s.x, s.y, s.z, s.w};
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * (BN / WN) + j * 32 + rc4;
-            const bool cok = col < p.Ncols;                   // Ncols % 4 == 0: all four columns or none
-            const long long coff = (long long)(col / p.L) * p.strideD_img + (col % p.L);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) cw[(8 * (r / 4) + 4 * lrow + (r % 4)) * CS + lcol] = acc[i][j][r];
-#pragma unroll
-                for (int ps = 0; ps < 4; ++ps) {
-                    const int row = ps * 8 + rrow;
-                    const int m = m0 + wm * (BM / WM) + i * 32 + row;
-                    float4 v = *reinterpret_cast<const float4*>(&cw[row * CS + rc4]);
-                    if (cok && m < p.M) {
-                        if (p.bias) {
-                            const float bv = p.bias[m];
-                            v.x += bv; v.y += bv; v.z += bv; v.w += bv;
-                        }
-                        *reinterpret_cast<float4*>(Db + coff + (long long)m * p.strideD_row) = v;
-                    }
-                }
-            }
-        }
-        return;
-    }
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * (BN / WN) + j * 32 + lcol;
-        if (col >= p.Ncols) continue;
-        const long long coff = (long long)(col / p.L) * p.strideD_img + (col % p.L);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int mbase = m0 + wm * (BM / WM) + i * 32 + 4 * lrow;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = mbase + 8 * (r / 4) + (r % 4);
-                if (m < p.M) {
-                    float v = acc[i][j][r];
-                    if (p.bias) v += p.bias[m];
-                    Db[coff + (long long)m * p.strideD_row] = v;
-                }
-            }
+        for (int e = 0; e < 4; ++e) {
+            const int col = c4 + e;
+            if (col < p.Ncols) Db[(long long)(col / p.L) * p.strideD_img + (col % p.L)] = o[e];
         }
     }
 }
@@ -436,24 +424,26 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
         // every slice needs at least one chunk, and the scratch buffers must be there
         const int all_chunks = (p.R + BK - 1) / BK;
         const int per_split = (all_chunks + splitk - 1) / splitk;
-        if ((long long)(splitk - 1) * per_split >= all_chunks || !p.splitk_partial || !p.splitk_counters || total * splitk >= (1ll << 31))
+        if ((long long)(splitk - 1) * per_split >= all_chunks || !p.splitk_partial || total * splitk >= (1ll << 31))
             return hipErrorInvalidValue;
     }
     const Extents ex = operand_extents(p);
     if (BUF && !ex.narrow) return hipErrorNotSupported;       // the caller falls back to the 64-bit loader
     const dim3 grid((unsigned)(total * splitk)), block(WM * WN * 64);
-    const int vecD = ((reinterpret_cast<uintptr_t>(p.D) & 15u) == 0 && p.L % 4 == 0 && p.Ncols % 4 == 0 && p.strideD_batch % 4 == 0 &&
-                      p.strideD_img % 4 == 0 && p.strideD_row % 4 == 0) ? 1 : 0;
+    const int vecD = result_rows_vectorisable(p);
+    const int ldc = gemm_splitk_ldc(p);
     if (p.gather)
         hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
-                           (int)total, ex.a_bytes, ex.b_bytes, vecD);
+                           (int)total, ex.a_bytes, ex.b_bytes, vecD, ldc);
     else if (vec)
         hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
-                           (int)total, ex.a_bytes, ex.b_bytes, vecD);
+                           (int)total, ex.a_bytes, ex.b_bytes, vecD, ldc);
     else
         hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
-                           (int)total, ex.a_bytes, ex.b_bytes, vecD);
-    return hipGetLastError();
+                           (int)total, ex.a_bytes, ex.b_bytes, vecD, ldc);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splitk == 1) return e;
+    return launch_splitk_reduce(p, s);
 }
 
 inline bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
@@ -509,11 +499,22 @@ bool gemm_variant_tile(int prec, int variant, int* bm, int* bn, int* bk)
     return prec == 0 ? gemm_f32_variant_tile(variant, bm, bn, bk) : gemm_bf16_variant_tile(variant, bm, bn, bk);
 }
 
-void gemm_splitk_workspace(const GemmProblem& p, int bm, int bn, int splitk, long long* partial_floats, long long* counters)
+long long gemm_splitk_workspace(const GemmProblem& p, int splitk)
 {
-    const long long tiles = (long long)((p.M + bm - 1) / bm) * ((p.Ncols + bn - 1) / bn) * p.batch;
-    *counters = tiles;
-    *partial_floats = tiles * splitk * bm * bn;
+    return (long long)splitk * p.batch * p.M * gemm_splitk_ldc(p);
+}
+
+hipError_t launch_splitk_reduce(const GemmProblem& p, hipStream_t s)
+{
+    if (p.splitk < 2 || !p.splitk_partial || !p.D) return hipErrorInvalidValue;
+    const int ldc = gemm_splitk_ldc(p);
+    const long long groups = (long long)p.batch * p.M * (ldc / 4);
+    if (groups <= 0 || (groups + 255) / 256 >= (1ll << 31)) return hipErrorInvalidValue;
+    GemmProblem q = p;
+    q.splitk = 1;                                   // vectorisability of D itself, not of the scratch tensor
+    const int vecD = result_rows_vectorisable(q);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, p, ldc, vecD);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s)

@@ -21,7 +21,7 @@
 // 8*(l/32) .. +7, column l%32) is four dwords, row pairs 4*(l/32) .. +3.
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
-#include "gemm_splitk.hpp"
+#include "gemm_epilogue.hpp"
 
 namespace mnnconv {
 namespace {
@@ -58,7 +58,8 @@ __device__ __forceinline__ void split_pair(float x0, float x1, unsigned* hi, uns
 
 // MODE 0: B element by element through (col / L, col % L); 1: 16-byte loads; 2: im2col gather.
 template <int BM, int BN, int BK, int WM, int WN, int MODE, bool SPLIT>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmProblem p, int tilesM, int tilesN, int total)
+__global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmProblem p, int tilesM, int tilesN, int total,
+                                                                 int vecD, int ldc)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM / 32;
@@ -72,8 +73,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmProblem p, 
     static_assert(A4 % NT == 0 && B4 % NT == 0, "tile must divide evenly over the workgroup");
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 16 == 0, "tile shape");
 
-    __shared__ __attribute__((aligned(16))) unsigned As[2][NP][RP][BM];
-    __shared__ __attribute__((aligned(16))) unsigned Bs[2][NP][RP][BN];
+    // one LDS block: operand double buffer during the reduction, staging tiles for the result stores after it
+    constexpr int AB_WORDS = 2 * NP * RP * (BM + BN);
+    constexpr int C_WORDS = (NT / 64) * kStageFloats;
+    __shared__ __attribute__((aligned(16))) unsigned smem[AB_WORDS > C_WORDS ? AB_WORDS : C_WORDS];
+    unsigned (*As)[NP][RP][BM] = reinterpret_cast<unsigned (*)[NP][RP][BM]>(smem);
+    unsigned (*Bs)[NP][RP][BN] = reinterpret_cast<unsigned (*)[NP][RP][BN]>(smem + 2 * NP * RP * BM);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -260,29 +265,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmProblem p, 
         __syncthreads();
     }
 
-    if (splitk > 1) {
-        if (!splitk_combine<TM, TN, NT>(acc, p.splitk_partial, p.splitk_counters, logical, split, splitk, tid)) return;
-    }
-    float* __restrict__ Db = p.D + (long long)b * p.strideD_batch;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * (BN / WN) + j * 32 + lcol;
-        if (col >= p.Ncols) continue;
-        const long long coff = (long long)(col / p.L) * p.strideD_img + (col % p.L);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int mbase = m0 + wm * (BM / WM) + i * 32 + 4 * lrow;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = mbase + 8 * (r / 4) + (r % 4);
-                if (m < p.M) {
-                    float v = acc[i][j][r];
-                    if (p.bias) v += p.bias[m];
-                    Db[coff + (long long)m * p.strideD_row] = v;
-                }
-            }
-        }
-    }
+    const TileDest dest = tile_dest(p, b, split, splitk, ldc);
+    store_tiles<TM, TN>(acc, dest, p.M, p.Ncols, m0 + wm * (BM / WM), n0 + wn * (BN / WN), lane,
+                        reinterpret_cast<float*>(smem) + wave * kStageFloats, vecD);
 }
 
 template <int BM, int BN, int BK, int WM, int WN>
@@ -297,25 +282,29 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
         // every slice needs at least one chunk, and the scratch buffers must be there
         const int all_chunks = (p.R + BK - 1) / BK;
         const int per_split = (all_chunks + splitk - 1) / splitk;
-        if ((long long)(splitk - 1) * per_split >= all_chunks || !p.splitk_partial || !p.splitk_counters || total * splitk >= (1ll << 31))
+        if ((long long)(splitk - 1) * per_split >= all_chunks || !p.splitk_partial || total * splitk >= (1ll << 31))
             return hipErrorInvalidValue;
     }
     const dim3 grid((unsigned)(total * splitk)), block(WM * WN * 64);
     const bool split = p.prec == 2;
+    const int vecD = result_rows_vectorisable(p);
+    const int ldc = gemm_splitk_ldc(p);
 #define MNN_LAUNCH(MODE_)                                                                                         \
     do {                                                                                                          \
         if (split)                                                                                                \
             hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, BK, WM, WN, MODE_, true>), grid, block, 0, s, p, tilesM,  \
-                               tilesN, (int)total);                                                               \
+                               tilesN, (int)total, vecD, ldc);                                                    \
         else                                                                                                      \
             hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, BK, WM, WN, MODE_, false>), grid, block, 0, s, p, tilesM, \
-                               tilesN, (int)total);                                                               \
+                               tilesN, (int)total, vecD, ldc);                                                    \
     } while (0)
     if (p.gather) MNN_LAUNCH(2);
     else if (vec) MNN_LAUNCH(1);
     else MNN_LAUNCH(0);
 #undef MNN_LAUNCH
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splitk == 1) return e;
+    return launch_splitk_reduce(p, s);
 }
 
 inline bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }

@@ -70,11 +70,10 @@ struct GemmProblem {
     int variant;                // 0 = choose from the shape; > 0 = a specific tile configuration (tuning, tests)
     int prec;                   // 0: fp32 MFMA; 1: bf16 operands; 2: bf16x3 (hi/lo split, three bf16 MFMAs per product)
     // Split-K (register-staged kernels only): splitk > 1 cuts the reduction of every tile into that many
-    // workgroups; needs splitk_partial (floats, see gemm_splitk_workspace) and splitk_counters (one zeroed
-    // unsigned per tile).  0 or 1 = off.
+    // workgroups, which write partial results to splitk_partial (gemm_splitk_workspace floats, 16-byte
+    // aligned); a second kernel adds them up in slice order.  0 or 1 = off.
     int splitk;
     float* splitk_partial;
-    unsigned* splitk_counters;
     // Implicit-GEMM gather for the sliding-window scheme (gather != 0): B is the input tensor x[N][C][H][W],
     // row r = (c, kr, ks), column = (img, oy, ox), element = x[img][c][oy*sh - ph + kr*dh][ox*sw - pw + ks*dw] or 0.
     // L must be H_o*W_o; the strideB_* fields are ignored.
@@ -92,7 +91,9 @@ const char* gemm_f32_variant_name(int variant);
 // Tile shape of a variant of precision `prec` (false for variants that cannot split K) and the scratch a
 // split-K launch needs: floats of partial sums and number of tile counters.
 bool gemm_variant_tile(int prec, int variant, int* bm, int* bn, int* bk);
-void gemm_splitk_workspace(const GemmProblem& p, int bm, int bn, int splitk, long long* partial_floats, long long* counters);
+inline int gemm_splitk_ldc(const GemmProblem& p) { return (p.Ncols + 3) / 4 * 4; }    // row length of the partial results
+long long gemm_splitk_workspace(const GemmProblem& p, int splitk);                    // floats
+hipError_t launch_splitk_reduce(const GemmProblem& p, hipStream_t s);
 // bf16 / bf16x3 operand kernels (gemm_bf16.hip); launch_gemm_f32 forwards to them when prec != 0
 int gemm_bf16_variant_count();
 const char* gemm_bf16_variant_name(int variant);
