@@ -14,6 +14,37 @@ struct ArenaBuffer {
     int first, last;   // index of the first and the last operator that touches the buffer, first <= last
 };
 
+// Second placement rule, used as a cross-check on the walk: buffers in order of decreasing size, each at
+// the lowest offset that is free over its whole lifetime.  It sees all lifetimes at once and so avoids the
+// holes a strictly chronological walk can leave behind a buffer that is still alive.
+inline long long place_by_size(const std::vector<ArenaBuffer>& bufs, const std::vector<long long>& size,
+                               std::vector<long long>* offsets)
+{
+    const int n = (int)bufs.size();
+    std::vector<int> order(n), placed;
+    for (int i = 0; i < n; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return size[a] > size[b]; });
+    offsets->assign(n, 0);
+    long long pool = 0;
+    for (int i : order) {
+        if (size[i] == 0) continue;
+        std::vector<std::pair<long long, long long>> busy;      // [begin, end) of placed buffers alive with i
+        for (int j : placed)
+            if (bufs[j].first <= bufs[i].last && bufs[i].first <= bufs[j].last)
+                busy.push_back(std::make_pair((*offsets)[j], (*offsets)[j] + size[j]));
+        std::sort(busy.begin(), busy.end());
+        long long off = 0;
+        for (const auto& iv : busy) {
+            if (off + size[i] <= iv.first) break;
+            off = std::max(off, iv.second);
+        }
+        (*offsets)[i] = off;
+        pool = std::max(pool, off + size[i]);
+        placed.push_back(i);
+    }
+    return pool;
+}
+
 // Writes one offset per buffer (multiples of `align`, a power of two) and the pool size.  Two buffers whose
 // lifetimes intersect never overlap in memory.  Returns false on malformed input.
 inline bool plan_arena(const std::vector<ArenaBuffer>& bufs, long long align, std::vector<long long>* offsets,
@@ -75,6 +106,12 @@ inline bool plan_arena(const std::vector<ArenaBuffer>& bufs, long long align, st
             if (size[i] > 0 && bufs[i].first == t) (*offsets)[i] = take(size[i]);
     }
     *total = pool;
+    std::vector<long long> alt;
+    const long long alt_pool = place_by_size(bufs, size, &alt);
+    if (alt_pool < pool) {
+        *offsets = alt;
+        *total = alt_pool;
+    }
     return true;
 }
 
