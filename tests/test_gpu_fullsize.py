@@ -73,3 +73,36 @@ def test_cfg5_sampled(layer):
     err = float(np.max(np.abs(got - ref))) / scale
     print(f"[sampled] {layer.name} {s.label(layer.kh)} err={err:.2e}", flush=True)
     assert err <= tol_for(s, layer.kh, m)
+
+
+def test_operands_of_two_gib_take_the_wide_loader():
+    """An input tensor of 2 GiB: past what the GEMM's range-checked 32-bit offsets can address, so the 1x1 and
+    the sliding-window schemes must switch to their 64-bit loader.  Oracle at sampled output coordinates."""
+    from conv_workloads import ConvLayer, BASE_SEED
+    m = mnn()
+    n, c, hw, k = 2, 16, 4096, 4
+    assert n * c * hw * hw * 4 >= 2**31
+    rng = np.random.Generator(np.random.PCG64(BASE_SEED + 9900))
+    x = rng.random((n, c, hw, hw), dtype=np.float32) * 2 - 1
+    xd = torch.from_numpy(x).cuda()
+    for name, ksz, stride, pad in (("wide_pw", 1, 1, 0), ("wide_k3s2", 3, 2, 1)):
+        layer = ConvLayer(name, n, c, hw, hw, k, ksz, ksz, stride, pad, 1, (-1.0, 1.0), BASE_SEED + 9901)
+        w = rng.normal(0, np.sqrt(2.0 / (ksz * ksz * c)), (k, c, ksz, ksz)).astype(np.float32)
+        b = rng.uniform(-0.1, 0.1, k).astype(np.float32)
+        wd, bd = torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda()
+        o = m.Options.defaults()
+        o.force_kind = m.SCHEME_GEMM1X1 if ksz == 1 else m.SCHEME_DIRECT
+        with m.ConvPlan.for_layer(layer, options=o) as plan:
+            y = torch.full(plan.out_shape, float("nan"), device="cuda")
+            plan.run(xd, wd, bd, y)
+            torch.cuda.synchronize()
+            desc = plan.describe()
+        coords = sample_coords(layer.out_shape, 2048, np.random.default_rng(5))
+        ref = oracle.conv2d_points(x, w, b, coords, stride=stride, pad=pad)
+        got = y[coords[:, 0], coords[:, 1], coords[:, 2], coords[:, 3]].cpu().numpy()
+        assert np.isfinite(got).all()
+        err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+        print(f"[wide] {name} {desc} err={err:.2e}", flush=True)
+        assert err <= 1e-4
+        assert bool(torch.isfinite(y).all())
+        del y
