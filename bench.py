@@ -128,6 +128,11 @@ def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
                  "planner_ms": {c.label(layer.kh): round(c.est_ms, 4) for c in plan.candidates if c.est_ms >= 0},
                  "stage_ms": {STAGE_NAMES[i]: round(ms[i], 5) for i in range(1, 4) if ms[i] > 0},
                  "filter_ms_one_off": round(ms[0], 5)}
+        if layer.kh == layer.kw and layer.kh > 1 and layer.stride == 1 and layer.dil == 1:
+            # Section 3.2 (1): the tile size the analytic cost would pick (1 = sliding window) next to the timed choice
+            entry["analytic_n"] = mnn.analytic_tile(layer.kh, layer.c_in, layer.c_out, layer.h_out, layer.w_out,
+                                                    mnn.Options.defaults().alpha_max)
+            entry["timed_n"] = sch.tile_n if sch.kind == mnn.SCHEME_WINOGRAD else 1
         lay_ms = sum(ms[1:4])
         entry["ms"] = round(lay_ms, 5)
         entry["gflops_direct_count"] = round(layer.direct_flops / (lay_ms * 1e-3) / 1e9, 1) if lay_ms > 0 else None
@@ -293,6 +298,7 @@ def main():
                         "stage_ms": e["stage_ms"]} for e in r["per_layer"]]}
     if not args.only_main:
         others = []
+        compared = [e for e in main_res["per_layer"] if "analytic_n" in e]
         for cfg in (1, 2, 3, 4, 5):
             if cfg == args.config:
                 continue
@@ -301,7 +307,13 @@ def main():
                            "ms_per_step": round(r["ms_per_step"], 5),
                            "layers": [{"layer": e["layer"], "scheme": e["scheme"], "ms": e["ms"], "stage_ms": e["stage_ms"],
                                        "stage_rate": e.get("stage_rate", {})} for e in r["per_layer"]]})
+            compared += [e for e in r["per_layer"] if "analytic_n" in e]
         out["other_workloads"] = others
+        # how often the analytic model of Section 3.2 (total cost over all tiles, alpha <= alpha_max) names the
+        # tile size that wins on the clock
+        out["analytic_vs_timed"] = {
+            "layers": len(compared), "same_n": sum(1 for e in compared if e["analytic_n"] == e["timed_n"]),
+            "detail": {e["layer"] + f"[{i}]": [e["analytic_n"], e["timed_n"]] for i, e in enumerate(compared)}}
         # preparation-execution decoupling over a chain of layers (the launch-bound batch-1 regime and batch 32)
         out["chained_execution"] = [run_chain("resnet18_trunk", b, 200 if b == 1 else 50, 10, stream, mnn, torch)
                                     for b in (1, 32)]
