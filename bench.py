@@ -35,10 +35,11 @@ def stage_work(layer, scheme, info, mnn):
     out = {}
     if scheme.kind == mnn.SCHEME_WINOGRAD:
         a, n, P = info["alpha"], info["tile_n"], info["p"]
-        a2 = a * a
-        out["input_transform"] = (4.0 * a ** 3 * C * P, 4.0 * (N * C * layer.h * layer.w + a2 * C * P))
+        aw, nw = info["alpha_w"], info["tile_n_w"]        # differ from a, n for kernels with one row or column
+        a2 = a * aw
+        out["input_transform"] = (2.0 * (a * a * aw + a * aw * aw) * C * P, 4.0 * (N * C * layer.h * layer.w + a2 * C * P))
         out["gemm"] = (2.0 * a2 * K * C * P, 4.0 * a2 * (K * C + C * P + K * P))
-        out["output_transform"] = (2.0 * (n * a2 + n * n * a) * K * P, 4.0 * (a2 * K * P + N * K * Ho * Wo))
+        out["output_transform"] = (2.0 * (n * a * aw + n * nw * aw) * K * P, 4.0 * (a2 * K * P + N * K * Ho * Wo))
     elif scheme.kind == mnn.SCHEME_GEMM1X1:
         HW = layer.h * layer.w
         out["gemm"] = (2.0 * N * K * C * HW, 4.0 * (N * C * HW + N * K * HW + K * C))
@@ -124,8 +125,8 @@ def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
         ms = plan.run_timed(xd, wd, bd, y, iters=iters, stream=stream)
         sch = plan.scheme
         sw = stage_work(layer, sch, plan.info, mnn)
-        entry = {"layer": layer.name, "scheme": sch.label(layer.kh), "kernels": plan.describe(),
-                 "planner_ms": {c.label(layer.kh): round(c.est_ms, 4) for c in plan.candidates if c.est_ms >= 0},
+        entry = {"layer": layer.name, "scheme": sch.label(layer.k_long), "kernels": plan.describe(),
+                 "planner_ms": {c.label(layer.k_long): round(c.est_ms, 4) for c in plan.candidates if c.est_ms >= 0},
                  "stage_ms": {STAGE_NAMES[i]: round(ms[i], 5) for i in range(1, 4) if ms[i] > 0},
                  "filter_ms_one_off": round(ms[0], 5)}
         if layer.kh == layer.kw and layer.kh > 1 and layer.stride == 1 and layer.dil == 1:
@@ -151,6 +152,24 @@ def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
     res["kernels"] = kernels
     for _, plan, *_rest in work:
         plan.close()
+    return res
+
+
+def run_rect(batch, stream, mnn, torch):
+    from conv_workloads import rect_layers, draw
+    res = []
+    for layer in rect_layers(batch):
+        x, w, b = (torch.from_numpy(a).cuda() for a in draw(layer))
+        entry = {"layer": layer.name}
+        for key, opt in (("planner", None), ("sliding_window", mnn.Options(force_kind=mnn.SCHEME_DIRECT))):
+            with mnn.ConvPlan.for_layer(layer, options=opt, stream=stream) as plan:
+                y = torch.empty(plan.out_shape, dtype=torch.float32, device="cuda")
+                ms = plan.run_timed(x, w, b, y, iters=20, stream=stream)
+                entry[key] = {"kernels": plan.describe(), "ms": round(sum(ms[1:4]), 5),
+                              "gflops_direct_count": round(layer.direct_flops / (sum(ms[1:4]) * 1e-3) / 1e9, 1)}
+                if opt is None:
+                    entry["planner_ms"] = {c.label(layer.k_long): round(c.est_ms, 4) for c in plan.candidates if c.est_ms >= 0}
+        res.append(entry)
     return res
 
 
@@ -315,6 +334,8 @@ def main():
             "layers": len(compared), "same_n": sum(1 for e in compared if e["analytic_n"] == e["timed_n"]),
             "detail": {e["layer"] + f"[{i}]": [e["analytic_n"], e["timed_n"]] for i, e in enumerate(compared)}}
         # preparation-execution decoupling over a chain of layers (the launch-bound batch-1 regime and batch 32)
+        # kernels with a single row or column (factorised 7-tap layers): planner's choice next to the sliding window
+        out["rectangular_kernels"] = run_rect(16, stream, mnn, torch)
         out["chained_execution"] = [run_chain("resnet18_trunk", b, 200 if b == 1 else 50, 10, stream, mnn, torch)
                                     for b in (1, 32)]
     if args.plan_file:

@@ -39,18 +39,27 @@ class ConvLayer:
     kh: int
     kw: int
     stride: int = 1
-    pad: int = 0
+    pad: object = 0              # int, or (pad_h, pad_w)
     dil: int = 1
     x_range: Tuple[float, float] = (-1.0, 1.0)
     seed: int = BASE_SEED
 
     @property
+    def pad_hw(self) -> Tuple[int, int]:
+        return tuple(self.pad) if isinstance(self.pad, (tuple, list)) else (self.pad, self.pad)
+
+    @property
     def h_out(self) -> int:
-        return (self.h + 2 * self.pad - self.dil * (self.kh - 1) - 1) // self.stride + 1
+        return (self.h + 2 * self.pad_hw[0] - self.dil * (self.kh - 1) - 1) // self.stride + 1
 
     @property
     def w_out(self) -> int:
-        return (self.w + 2 * self.pad - self.dil * (self.kw - 1) - 1) // self.stride + 1
+        return (self.w + 2 * self.pad_hw[1] - self.dil * (self.kw - 1) - 1) // self.stride + 1
+
+    @property
+    def k_long(self) -> int:
+        """Taps along the longer side of the kernel (the k of F(n, k) for square and single-row/column kernels)."""
+        return max(self.kh, self.kw)
 
     @property
     def out_shape(self) -> Tuple[int, int, int, int]:
@@ -168,4 +177,21 @@ def small_parity_layers() -> List[ConvLayer]:
         L(11, "multi_tile_k3", 2, 70, 30, 34, 130, 3, 3, 1, 1),
         L(12, "rect_1x7", 1, 5, 9, 20, 6, 1, 7, 1, 0),
         L(13, "pad_bigger_than_needed", 1, 4, 8, 8, 4, 3, 3, 1, 2),
+        L(14, "rect_7x1_same", 2, 6, 17, 13, 9, 7, 1, 1, (3, 0)),
+        L(15, "rect_1x3_same", 2, 10, 9, 22, 5, 1, 3, 1, (0, 1)),
+        L(16, "rect_5x1_nopad", 1, 3, 23, 6, 4, 5, 1, 1, 0),
+        L(17, "rect_3x5_direct_only", 1, 4, 10, 12, 3, 3, 5, 1, (1, 2)),
+    ]
+
+
+def rect_layers(n: int = 16) -> List[ConvLayer]:
+    """Factorised 7-tap layers (1x7 then 7x1, 'same' padding) on a 17x17 map, the shape of the
+    Inception-style blocks the paper's benchmark networks contain; seeded like the workload families."""
+    def L(i, name, c, k, kh, kw, pad):
+        return ConvLayer(name, n, c, 17, 17, k, kh, kw, 1, pad, 1, (-1.0, 1.0), BASE_SEED + 9700 + i)
+    return [
+        L(0, "incep128_17x17_1x7", 128, 128, 1, 7, (0, 3)),
+        L(1, "incep128_17x17_7x1", 128, 128, 7, 1, (3, 0)),
+        L(2, "incep192_17x17_1x7", 192, 192, 1, 7, (0, 3)),
+        L(3, "incep192_17x17_7x1", 192, 192, 7, 1, (3, 0)),
     ]

@@ -113,11 +113,19 @@ bool is_pointwise(const Layer& L)
     return L.s.kh == 1 && L.s.kw == 1 && L.g.stride_h == 1 && L.g.stride_w == 1 && L.g.pad_h == 0 && L.g.pad_w == 0;
 }
 
+// kernels with a single row or column (1 x k, k x 1, k >= 2): one-dimensional Winograd along the long axis
+bool winograd_rect(const Layer& L)
+{
+    return (L.s.kh == 1) != (L.s.kw == 1);
+}
+
 bool winograd_admissible(const Layer& L)
 {
-    return L.s.kh == L.s.kw && L.s.kh >= 2 && L.g.stride_h == 1 && L.g.stride_w == 1 && L.g.dil_h == 1 &&
-           L.g.dil_w == 1;
+    const bool shape_ok = (L.s.kh == L.s.kw && L.s.kh >= 2) || winograd_rect(L);
+    return shape_ok && L.g.stride_h == 1 && L.g.stride_w == 1 && L.g.dil_h == 1 && L.g.dil_w == 1;
 }
+
+int wino_k(const Layer& L) { return L.s.kh > L.s.kw ? L.s.kh : L.s.kw; }    // taps along the transformed axis
 
 mnn_scheme make_scheme(int kind, int n, int prec, int variant = 0)
 {
@@ -155,8 +163,15 @@ std::vector<mnn_scheme> enumerate(const Layer& L, const mnn_conv_options& o)
     }
     if (is_pointwise(L)) return out;
     if (winograd_admissible(L)) {
-        const int k = L.s.kh;
+        const int k = wino_k(L);
         for (int n = 2; n + k - 1 <= o.alpha_max; ++n) {
+            if (winograd_rect(L)) {          // transforms and GEMM as separate kernels only
+                if (winograd_kernels_available(n, k)) {
+                    out.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, MNN_GEMM_FP32, MNN_WINO_UNFUSED));
+                    if (o.allow_bf16) out.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, MNN_GEMM_BF16X3, MNN_WINO_UNFUSED));
+                }
+                continue;
+            }
             push_wino_variants(&out, n, k, MNN_GEMM_FP32);
             if (o.allow_bf16 && winograd_kernels_available(n, k))
                 out.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, MNN_GEMM_BF16X3, MNN_WINO_UNFUSED));
@@ -316,7 +331,9 @@ int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
 struct Impl {
     mnn_scheme scheme{};
     Layer L{};
-    WinogradMatrices mats;
+    WinogradMatrices mats;      // along H (both axes of a square kernel)
+    WinogradMatrices mats_w;    // along W (kernels with one row or column; the untransformed axis holds 1 x 1 identities)
+    bool rect = false;
     WinoGeom wg{};
     float* U = nullptr; size_t U_bytes = 0;
     float* V = nullptr; size_t V_bytes = 0;
@@ -384,20 +401,30 @@ struct Impl {
         if (s.prec != MNN_GEMM_FP32 && s.kind == MNN_SCHEME_WINOGRAD && s.variant != MNN_WINO_UNFUSED)
             return fail(MNN_E_UNSUPPORTED, "the fused Winograd kernels multiply in fp32 only");
         if (s.kind == MNN_SCHEME_WINOGRAD) {
-            if (!winograd_admissible(L)) return fail(MNN_E_UNSUPPORTED, "Winograd needs a square kernel >= 2, stride 1, dilation 1");
-            const int n = s.tile_n, k = sh.kh;
+            if (!winograd_admissible(L))
+                return fail(MNN_E_UNSUPPORTED, "Winograd needs a square kernel >= 2 (or 1 x k / k x 1), stride 1, dilation 1");
+            rect = winograd_rect(L);
+            const int n = s.tile_n, k = wino_k(L);
             if (!winograd_kernels_available(n, k))
                 return fail(MNN_E_UNSUPPORTED, "F(%d,%d) is outside the built range (n 2..8, k 2..7, alpha <= %d)", n, k, kMaxAlphaT);
-            if (!generate_winograd(n, k, (double)o.point_scale_f, &mats))
+            WinogradMatrices gen, unit;
+            if (!generate_winograd(n, k, (double)o.point_scale_f, &gen))
                 return fail(MNN_E_UNSUPPORTED, "generator rejected F(%d,%d)", n, k);
+            unit.n = unit.k = unit.alpha = 1;
+            unit.AT.assign(1, 1.f); unit.G.assign(1, 1.f); unit.BT.assign(1, 1.f);
+            mats = (rect && sh.kh == 1) ? unit : gen;
+            mats_w = (rect && sh.kw == 1) ? unit : gen;
             wg.N = sh.n; wg.C = sh.c_in; wg.H = sh.h; wg.W = sh.w; wg.K = sh.c_out;
             wg.Ho = L.Ho; wg.Wo = L.Wo; wg.pad_h = L.g.pad_h; wg.pad_w = L.g.pad_w;
-            wg.n = n; wg.k = k; wg.alpha = n + k - 1;
-            wg.th = (L.Ho + n - 1) / n; wg.tw = (L.Wo + n - 1) / n;
+            wg.n = mats.n; wg.k = mats.k; wg.alpha = mats.alpha;
+            wg.nw = mats_w.n; wg.kw = mats_w.k; wg.alpha_w = mats_w.alpha;
+            wg.th = (L.Ho + wg.n - 1) / wg.n; wg.tw = (L.Wo + wg.nw - 1) / wg.nw;
             const long long P = (long long)sh.n * wg.th * wg.tw;
             if (P >= (1ll << 30)) return fail(MNN_E_UNSUPPORTED, "too many tiles");
             wg.P = (int)P; wg.ldp = round_up(wg.P, 4); wg.ldk = ldk;
-            const size_t a2 = (size_t)wg.alpha * wg.alpha;
+            const size_t a2 = (size_t)wg.alpha * wg.alpha_w;
+            if (rect && s.variant != MNN_WINO_UNFUSED)
+                return fail(MNN_E_UNSUPPORTED, "kernels with one row or column have no fused variant");
             if (!wino_variant_available(n, k, s.variant))
                 return fail(MNN_E_UNSUPPORTED, "Winograd variant %d is not available for F(%d,%d)", s.variant, n, k);
             int rc;
@@ -447,7 +474,7 @@ struct Impl {
     {
         GemmProblem p{};
         p.At = U; p.B = V; p.D = M; p.bias = nullptr;
-        p.M = wg.K; p.Ncols = wg.ldp; p.R = wg.C; p.batch = wg.alpha * wg.alpha;
+        p.M = wg.K; p.Ncols = wg.ldp; p.R = wg.C; p.batch = wg.alpha * wg.alpha_w;
         p.lda = ldk; p.L = wg.ldp;
         p.strideA_batch = (long long)wg.C * ldk;
         p.strideB_batch = (long long)wg.C * wg.ldp; p.strideB_img = 0; p.strideB_row = wg.ldp;
@@ -567,8 +594,14 @@ struct Impl {
         const mnn_conv_shape& sh = L.s;
         if (scheme.kind == MNN_SCHEME_WINOGRAD) {
             switch (st) {
-                case MNN_STAGE_FILTER: e = launch_filter_transform(wg, mats.G.data(), w, U, s); break;
-                case MNN_STAGE_INPUT: e = launch_input_transform(wg, mats.BT.data(), x, V, s); break;
+                case MNN_STAGE_FILTER:
+                    e = rect ? launch_filter_transform_rect(wg, mats.G.data(), mats_w.G.data(), w, U, s)
+                             : launch_filter_transform(wg, mats.G.data(), w, U, s);
+                    break;
+                case MNN_STAGE_INPUT:
+                    e = rect ? launch_input_transform_rect(wg, mats.BT.data(), mats_w.BT.data(), x, V, s)
+                             : launch_input_transform(wg, mats.BT.data(), x, V, s);
+                    break;
                 case MNN_STAGE_GEMM: {
                     if (scheme.variant != MNN_WINO_UNFUSED) {
                         e = launch_wino_fused(wg, scheme.variant - 1, mats.AT.data(), U, V, b, y, s);
@@ -577,7 +610,10 @@ struct Impl {
                     e = launch_gemm_f32(wino_gemm_problem(), s);
                     break;
                 }
-                case MNN_STAGE_OUTPUT: e = launch_output_transform(wg, mats.AT.data(), M, b, y, s); break;
+                case MNN_STAGE_OUTPUT:
+                    e = rect ? launch_output_transform_rect(wg, mats.AT.data(), mats_w.AT.data(), M, b, y, s)
+                             : launch_output_transform(wg, mats.AT.data(), M, b, y, s);
+                    break;
             }
         } else if (scheme.kind == MNN_SCHEME_GEMM1X1) {
             const int HW = sh.h * sh.w;
@@ -606,7 +642,9 @@ void describe_impl(const Impl& im, char* buf, size_t cap)
     const char* gv = gvs.c_str();
     switch (im.scheme.kind) {
         case MNN_SCHEME_WINOGRAD:
-            if (im.scheme.variant == MNN_WINO_UNFUSED)
+            if (im.rect)
+                std::snprintf(buf, cap, "F(%dx%d,%dx%d) unfused gemm=%s", im.wg.n, im.wg.nw, im.wg.k, im.wg.kw, gv);
+            else if (im.scheme.variant == MNN_WINO_UNFUSED)
                 std::snprintf(buf, cap, "F(%d,%d) unfused gemm=%s", im.wg.n, im.wg.k, gv);
             else
                 std::snprintf(buf, cap, "F(%d,%d) fused-output %s", im.wg.n, im.wg.k,
@@ -780,11 +818,13 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
         if (o.force_kind == MNN_SCHEME_WINOGRAD) {
             int n = o.force_tile_n;
             if (n <= 0) {
-                n = analytic_tile(L.s.kh, L.s.c_in, L.s.c_out, L.Ho, L.Wo, o.alpha_max);
+                n = analytic_tile(wino_k(L), L.s.c_in, L.s.c_out, L.Ho, L.Wo, o.alpha_max);
                 if (n < 2) n = 2;
             }
             if (o.force_variant >= 0)
                 plan->cands.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, o.force_prec, o.force_variant));
+            else if (winograd_admissible(L) && winograd_rect(L))
+                plan->cands.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, o.force_prec, MNN_WINO_UNFUSED));
             else if (winograd_admissible(L))
                 push_wino_variants(&plan->cands, n, L.s.kh, o.force_prec);   // time the arrangements of this F(n,k)
             if (plan->cands.empty()) plan->cands.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, o.force_prec, 0));
@@ -825,7 +865,7 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
                     if (rc == MNN_E_OOM) { c.est_ms = -1.f; (void)hipGetLastError(); continue; }   // does not fit: not a candidate
                     if (rc) { delete plan; return rc; }
                 }
-                const int pick = select_scheme(plan->cands.data(), (int)plan->cands.size(), L.s.kh);
+                const int pick = select_scheme(plan->cands.data(), (int)plan->cands.size(), wino_k(L));
                 if (pick < 0) { delete plan; return fail(MNN_E_OOM, "no candidate scheme could be timed"); }
                 chosen = plan->cands[pick];
             }
@@ -903,6 +943,7 @@ int mnn_conv_plan_info(mnn_conv_plan_t plan, mnn_plan_info* out)
     const Impl& im = plan->impl;
     if (im.scheme.kind == MNN_SCHEME_WINOGRAD) {
         out->alpha = im.wg.alpha; out->tile_n = im.wg.n; out->tiles_h = im.wg.th; out->tiles_w = im.wg.tw;
+        out->alpha_w = im.wg.alpha_w; out->tile_n_w = im.wg.nw;
         out->p = im.wg.P; out->ldp = im.wg.ldp; out->kg = im.wg.kg; out->pg = im.wg.pg;
     }
     out->ldk = im.ldk;

@@ -19,8 +19,10 @@ struct WinoGeom {
     int N, C, H, W, K;          // input x[N][C][H][W], K output channels
     int Ho, Wo;                 // output plane
     int pad_h, pad_w;
-    int n, k, alpha;            // F(n, k), alpha = n + k - 1
-    int th, tw;                 // tiles per image: ceil(Ho/n), ceil(Wo/n)
+    int n, k, alpha;            // F(n, k), alpha = n + k - 1 (along H when the kernel is not square)
+    int nw, kw, alpha_w;        // the same along W; equal to n, k, alpha for square kernels.  An axis along
+                                // which the kernel has one tap is left untransformed: n = k = alpha = 1.
+    int th, tw;                 // tiles per image: ceil(Ho/n), ceil(Wo/nw)
     int P;                      // N * th * tw
     int ldp;                    // row length of V / M rows (P rounded up to 4)
     int ldk;                    // row length of U rows (K rounded up to 4)
@@ -44,6 +46,17 @@ hipError_t launch_output_transform(const WinoGeom& g, const float* AT /*host, n 
                                    const float* M, const float* bias, float* y, hipStream_t s);
 
 bool winograd_kernels_available(int n, int k);
+
+// One-dimensional Winograd for kernels with a single row or column (1 x k, k x 1; Section 3.3.1: "kernels of
+// any size"): F(n, k) along the long axis, identity along the other.  Row layouts only (g.blocked == 0):
+// U[(i*alpha_w + j)][c][ldk], V and M likewise.  Matrices of the untransformed axis are the 1 x 1 identity.
+bool winograd_rect_kernels_available(int nh, int kh, int nw, int kw);
+hipError_t launch_filter_transform_rect(const WinoGeom& g, const float* Gh, const float* Gw, const float* w, float* U,
+                                        hipStream_t s);
+hipError_t launch_input_transform_rect(const WinoGeom& g, const float* BTh, const float* BTw, const float* x, float* V,
+                                       hipStream_t s);
+hipError_t launch_output_transform_rect(const WinoGeom& g, const float* ATh, const float* ATw, const float* M,
+                                        const float* bias, float* y, hipStream_t s);
 
 // Winograd-domain product with the inverse transform and bias fused in:
 // y = A^T [ sum_c U (.) V ] A + bias, operands in the blocked layout.  M is never stored.

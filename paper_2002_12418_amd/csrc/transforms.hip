@@ -279,6 +279,7 @@ bool geom_ok(const WinoGeom& g)
 {
     if (g.N <= 0 || g.C <= 0 || g.H <= 0 || g.W <= 0 || g.K <= 0) return false;
     if (g.n < 2 || g.k < 2 || g.k > kMaxK || g.alpha != g.n + g.k - 1 || g.alpha > kMaxAlphaT) return false;
+    if (g.nw != g.n || g.kw != g.k || g.alpha_w != g.alpha) return false;      // square kernels only here
     if (g.Ho != g.H + 2 * g.pad_h - g.k + 1 || g.Wo != g.W + 2 * g.pad_w - g.k + 1) return false;
     if (g.Ho <= 0 || g.Wo <= 0) return false;
     if (g.th != (g.Ho + g.n - 1) / g.n || g.tw != (g.Wo + g.n - 1) / g.n) return false;

@@ -77,12 +77,21 @@ def test_enumeration_rules(mnn):
     # k = 1, stride 1, no padding -> one matrix multiplication
     c = mnn.enumerate_schemes(16, 32, 112, 112, 64, 1, 1)
     assert [s.kind for s in c] == [mnn.SCHEME_GEMM1X1]
-    # stride 2 / dilation 2 / rectangular kernel -> sliding window only
+    # stride 2 / dilation 2 / a kernel that is neither square nor a single row or column -> sliding window only
     for kw in (dict(stride=2, pad=1), dict(dil=2, pad=2)):
         c = mnn.enumerate_schemes(1, 64, 56, 56, 128, 3, 3, **kw)
         assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
-    c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 1, 7)
+    c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 3, 5)
     assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
+    c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 1, 7, stride=(1, 2))
+    assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
+    # a single row or column of k taps: sliding window + one-dimensional F(n, k), unfused only
+    for kh, kwid in ((1, 7), (7, 1)):
+        c = mnn.enumerate_schemes(1, 8, 20, 20, 8, kh, kwid)
+        assert c[0].kind == mnn.SCHEME_DIRECT
+        assert [(s.kind, s.tile_n, s.variant) for s in c[1:]] == [(mnn.SCHEME_WINOGRAD, 2, mnn.WINO_UNFUSED)]
+    c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 3, 1, pad=(1, 0))
+    assert [(s.tile_n, s.variant) for s in c if s.kind == mnn.SCHEME_WINOGRAD] == [(n, mnn.WINO_UNFUSED) for n in range(2, 7)]
     # 3x3 stride 1: sliding window + F(n,3) for n = 2..6 (alpha <= 8), each in its kernel arrangements
     c = mnn.enumerate_schemes(1, 64, 56, 56, 64, 3, 3, pad=1)
     assert c[0].kind == mnn.SCHEME_DIRECT

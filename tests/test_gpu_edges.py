@@ -55,7 +55,7 @@ def test_guard_bands_and_unaligned_bases(layer, shift):
 
     (_, xd), (_, wd), (_, bd) = place(x), place(w), place(b)
     for s, opt in all_forced(m, layer):
-        print(f"[case] {layer.name} shift={shift} {s.label(layer.kh)}", flush=True)
+        print(f"[case] {layer.name} shift={shift} {s.label(layer.k_long)}", flush=True)
         ybuf = torch.full((ref.size + 2 * guard,), 777.0, device="cuda")
         y = ybuf[guard:guard + ref.size].view(ref.shape)
         with m.ConvPlan.for_layer(layer, options=opt) as plan:
@@ -63,7 +63,7 @@ def test_guard_bands_and_unaligned_bases(layer, shift):
             torch.cuda.synchronize()
         host = ybuf.cpu().numpy()
         assert np.all(host[:guard] == 777.0) and np.all(host[guard + ref.size:] == 777.0), "wrote outside the output"
-        assert oracle.error_ratio(host[guard:guard + ref.size].reshape(ref.shape), ref) <= tol_for(s, layer.kh, m)
+        assert oracle.error_ratio(host[guard:guard + ref.size].reshape(ref.shape), ref) <= tol_for(s, layer.k_long, m)
 
 
 def test_large_alpha_and_point_scale():

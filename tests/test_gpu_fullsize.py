@@ -35,8 +35,8 @@ def test_cfg3_cfg4_full_tensor(layer):
     got = y.cpu().numpy()
     assert np.isfinite(got).all()
     err = oracle.error_ratio(got, ref)
-    print(f"[full] {layer.name} {s.label(layer.kh)} err={err:.2e}", flush=True)
-    assert err <= tol_for(s, layer.kh, m)
+    print(f"[full] {layer.name} {s.label(layer.k_long)} err={err:.2e}", flush=True)
+    assert err <= tol_for(s, layer.k_long, m)
 
 
 def sample_coords(shape, count, rng):
@@ -71,8 +71,8 @@ def test_cfg5_sampled(layer):
     got = y.cpu().numpy()[coords[:, 0], coords[:, 1], coords[:, 2], coords[:, 3]].astype(np.float64)
     scale = float(torch.max(torch.abs(y)).item())
     err = float(np.max(np.abs(got - ref))) / scale
-    print(f"[sampled] {layer.name} {s.label(layer.kh)} err={err:.2e}", flush=True)
-    assert err <= tol_for(s, layer.kh, m)
+    print(f"[sampled] {layer.name} {s.label(layer.k_long)} err={err:.2e}", flush=True)
+    assert err <= tol_for(s, layer.k_long, m)
 
 
 def test_operands_of_two_gib_take_the_wide_loader():

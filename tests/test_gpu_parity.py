@@ -31,7 +31,7 @@ def forced_options(layer):
     out = []
     for s in m.enumerate_schemes(layer.n, layer.c_in, layer.h, layer.w, layer.c_out, layer.kh, layer.kw,
                                  stride=layer.stride, pad=layer.pad, dil=layer.dil):
-        out.append((s.label(layer.kh), m.Options(force_kind=s.kind, force_tile_n=s.tile_n, force_prec=s.prec,
+        out.append((s.label(layer.k_long), m.Options(force_kind=s.kind, force_tile_n=s.tile_n, force_prec=s.prec,
                                                  force_variant=s.variant)))
     return out
 
@@ -58,7 +58,7 @@ def test_small_layers_every_scheme(layer):
     for label, opt in forced_options(layer):
         print(f"[case] {layer.name} {label}", flush=True)
         err, scheme = run_and_compare(layer, opt)
-        assert err <= tol_for(scheme, layer.kh), (layer.name, label, err)
+        assert err <= tol_for(scheme, layer.k_long), (layer.name, label, err)
 
 
 @pytest.mark.parametrize("layer", small_parity_layers()[:4], ids=lambda l: l.name)
@@ -66,7 +66,7 @@ def test_small_layers_no_bias(layer):
     for label, opt in forced_options(layer):
         print(f"[case] nobias {layer.name} {label}", flush=True)
         err, scheme = run_and_compare(layer, opt, with_bias=False)
-        assert err <= tol_for(scheme, layer.kh), (layer.name, label, err)
+        assert err <= tol_for(scheme, layer.k_long), (layer.name, label, err)
 
 
 @pytest.mark.parametrize("layer", config_layers(1) + config_layers(2), ids=lambda l: l.name)
@@ -74,7 +74,7 @@ def test_config1_and_2_every_scheme(layer):
     for label, opt in forced_options(layer):
         print(f"[case] {layer.name} {label}", flush=True)
         err, scheme = run_and_compare(layer, opt)
-        assert err <= tol_for(scheme, layer.kh), (layer.name, label, err)
+        assert err <= tol_for(scheme, layer.k_long), (layer.name, label, err)
 
 
 @pytest.mark.parametrize("layer", config_layers(1) + config_layers(2), ids=lambda l: l.name)
@@ -82,7 +82,7 @@ def test_planner_choice_is_correct_and_listed(layer):
     m = mnn()
     m.cache_clear()
     err, scheme = run_and_compare(layer, None)
-    assert err <= tol_for(scheme, layer.kh)
+    assert err <= tol_for(scheme, layer.k_long)
     if layer.stride != 1:
         assert scheme.kind == m.SCHEME_DIRECT
 
@@ -101,11 +101,11 @@ def test_bf16_matrix_core_schemes(layer):
                                  stride=layer.stride, pad=layer.pad, dil=layer.dil, options=m.Options(allow_bf16=1)):
         if s.prec == m.GEMM_FP32:
             continue
-        print(f"[case] {layer.name} {s.label(layer.kh)}", flush=True)
+        print(f"[case] {layer.name} {s.label(layer.k_long)}", flush=True)
         opt = m.Options(force_kind=s.kind, force_tile_n=s.tile_n, force_prec=s.prec, force_variant=s.variant)
         err, scheme = run_and_compare(layer, opt)
         assert scheme.prec == s.prec
-        assert err <= (BF16X3_TOL if s.prec == m.GEMM_BF16X3 else BF16_TOL), (layer.name, s.label(layer.kh), err)
+        assert err <= (BF16X3_TOL if s.prec == m.GEMM_BF16X3 else BF16_TOL), (layer.name, s.label(layer.k_long), err)
         seen += 1
     assert seen >= 2
 
@@ -115,5 +115,5 @@ def test_planner_with_bf16_allowed_stays_within_the_bf16_bound():
     m.cache_clear()
     for layer in config_layers(2)[:5]:
         err, scheme = run_and_compare(layer, m.Options(allow_bf16=1))
-        assert err <= (tol_for(scheme, layer.kh) if scheme.prec == m.GEMM_FP32 else BF16_TOL)
+        assert err <= (tol_for(scheme, layer.k_long) if scheme.prec == m.GEMM_FP32 else BF16_TOL)
     m.cache_clear()

@@ -90,3 +90,42 @@ def test_blocked_stage_buffers(case):
     for full, lim in ((Ufull, (C, K)), (Vfull, (C, P))):
         assert np.all(full[:, :, lim[0]:, :] == 0) and np.all(full[:, :, :, lim[1]:] == 0)
     assert oracle.error_ratio(y.cpu().numpy(), yref) < 1e-4
+
+
+RECT_CASES = [
+    # n, kh, kw, N, C, H, W, K, pad
+    (2, 1, 7, 1, 5, 9, 20, 6, (0, 3)),
+    (2, 7, 1, 2, 6, 17, 13, 9, (3, 0)),
+    (4, 1, 3, 2, 10, 9, 22, 5, (0, 1)),
+    (6, 3, 1, 1, 7, 20, 5, 4, (1, 0)),
+    (4, 5, 1, 1, 3, 23, 6, 4, (0, 0)),
+]
+
+
+@pytest.mark.parametrize("case", RECT_CASES)
+def test_single_row_or_column_stage_buffers(case):
+    """Kernels with one row or column: U, V, M hold alpha_h x alpha_w positions, one of the two equal to 1."""
+    m = mnn()
+    n, kh, kw, N, C, H, W, K, pad = case
+    layer = ConvLayer("t", N, C, H, W, K, kh, kw, 1, pad, 1, (-1.0, 1.0), BASE_SEED + 600 + n + 7 * kh + kw)
+    x, w, b = draw(layer)
+    yref, st = winograd.winograd_conv2d(x, w, b, n, pad=pad, return_stages=True)
+    ah, aw = st["U"].shape[:2]
+    xd, wd, bd = (torch.from_numpy(t).cuda() for t in (x, w, b))
+    opt = m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=n, force_variant=m.WINO_UNFUSED)
+    with m.ConvPlan.for_layer(layer, options=opt) as plan:
+        info = plan.info
+        assert (info["alpha"], info["alpha_w"]) == (ah, aw)
+        assert (info["tile_n"], info["tile_n_w"]) == ((1, n) if kh == 1 else (n, 1))
+        y = plan.run(xd, wd, bd)
+        torch.cuda.synchronize()
+        P, ldp, ldk = info["p"], info["ldp"], info["ldk"]
+        assert P == st["V"].shape[-1]
+        U = plan.buffer_to_numpy(m.BUF_U).reshape(ah * aw, C, ldk)
+        V = plan.buffer_to_numpy(m.BUF_V).reshape(ah * aw, C, ldp)
+        M = plan.buffer_to_numpy(m.BUF_M).reshape(ah * aw, K, ldp)
+        assert "x" in plan.describe()
+    assert relerr(U[:, :, :K], st["U"].reshape(ah * aw, K, C).transpose(0, 2, 1)) < 1e-5
+    assert relerr(V[:, :, :P], st["V"].reshape(ah * aw, C, P)) < 1e-5
+    assert relerr(M[:, :, :P], st["M"].reshape(ah * aw, K, P)) < 1e-4
+    assert oracle.error_ratio(y.cpu().numpy(), oracle.conv2d(x, w, b, pad=pad)) < (1e-3 if ah * aw > 6 else 1e-4)

@@ -42,3 +42,34 @@ def test_no_bias():
     x, w, _ = draw(layer)
     ref = oracle.conv2d(x, w, None, pad=1)
     assert oracle.error_ratio(winograd.winograd_conv2d(x, w, None, 4, pad=1), ref) < 1e-12
+
+
+RECT_CASES = [
+    # n, kh, kw, N, C, H, W, K, pad
+    (2, 1, 7, 1, 3, 9, 20, 2, (0, 3)),
+    (2, 7, 1, 2, 2, 17, 13, 3, (3, 0)),
+    (4, 1, 3, 2, 4, 9, 22, 3, (0, 1)),     # ragged along W: 22 = 5*4 + 2
+    (6, 3, 1, 1, 2, 20, 5, 2, (1, 0)),     # ragged along H
+    (4, 5, 1, 1, 3, 23, 6, 4, (0, 0)),     # no padding
+    (3, 1, 2, 1, 2, 6, 11, 2, (0, 0)),     # even kernel
+]
+
+
+@pytest.mark.parametrize("case", RECT_CASES)
+def test_single_row_or_column_kernels_equal_definition(case):
+    """One-dimensional F(n, k) along the long side, identity along the other: still the plain convolution."""
+    n, kh, kw, N, C, H, W, K, pad = case
+    layer = ConvLayer("t", N, C, H, W, K, kh, kw, 1, pad, 1, (-1.0, 1.0), BASE_SEED + 177 + n + kh * 7 + kw)
+    x, w, b = draw(layer)
+    ref = oracle.conv2d(x, w, b, stride=1, pad=pad)
+    y, st = winograd.winograd_conv2d(x, w, b, n, pad=pad, return_stages=True)
+    assert y.shape == ref.shape
+    assert oracle.error_ratio(y, ref) < 1e-11
+    ah, aw = (1, n + kw - 1) if kh == 1 else (n + kh - 1, 1)
+    th, tw = (layer.h_out, -(-layer.w_out // n)) if kh == 1 else (-(-layer.h_out // n), layer.w_out)
+    assert st["U"].shape == (ah, aw, K, C)
+    assert st["V"].shape == (ah, aw, C, N * th * tw)
+    # along the untransformed side the transforms are the identity: U is G applied to the kernel's one line
+    line = w[:, :, 0, :] if kh == 1 else w[:, :, :, 0]
+    g = st["G_w"] if kh == 1 else st["G"]
+    assert np.allclose(st["U"].reshape(max(ah, aw), K, C), np.einsum("ir,kcr->ikc", g, line), rtol=0, atol=1e-14)
