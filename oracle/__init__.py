@@ -8,6 +8,7 @@ Contents
   conv_direct.c   float64 convolution straight from the definition (C, OpenMP)
   cook_toom.py    exact-rational Winograd/Cook-Toom matrices for F(n, k)
   winograd.py     float64 Winograd convolution taken step by step (Section 3.3.1)
+  memory_plan.py  checker for the memory pool of a chain of operators (Section 3.2)
   cost_model.py   the analytic scheme-selection cost (Section 3.2) and the
                   Strassen stop rule (Section 3.3.2)
 
