@@ -173,6 +173,34 @@ def run_rect(batch, stream, mnn, torch):
     return res
 
 
+def run_strassen(mnn, torch):
+    """Section 3.3.2 / Table 3 on this device: the plain fp32 product against 1 and 2 levels of Strassen, on the
+    paper's sizes and on sizes where the matrix cores, not launch latency, set the time.  (a, b, c) = [a,b] x [b,c]."""
+    res = []
+    for (M, R, N) in [(512, 512, 512), (1024, 1024, 1024), (1024, 1024, 784), (4096, 4096, 4096), (8192, 8192, 8192)]:
+        At = torch.randn(R, M, device="cuda")
+        B = torch.rand(R, N, device="cuda")
+        D = torch.empty(M, N, device="cuda")
+        entry = {"size": [M, R, N], "levels_by_rule": mnn.strassen_levels_by_rule(M, R, N, 8), "ms": {}}
+        for lv in (0, 1, 2):
+            if mnn.strassen_levels_by_rule(M, R, N, lv) < lv:
+                continue
+            with mnn.StrassenGemm(M, N, R, lv) as sg:
+                sg.set_left(At)
+                iters = 50 if M <= 2048 else 8
+                for _ in range(3):
+                    sg.run(B, D)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(iters):
+                    sg.run(B, D)
+                torch.cuda.synchronize()
+                entry["ms"][str(lv)] = round((time.perf_counter() - t0) / iters * 1e3, 4)
+        entry["plain_TFLOP/s"] = round(2.0 * M * R * N / (entry["ms"]["0"] * 1e-3) / 1e12, 1)
+        res.append(entry)
+    return res
+
+
 def run_chain(kind, batch, steps, warmup, stream, mnn, torch):
     """Chained execution of `kind` at `batch`: the same layers run (a) one plan at a time, each with memory of
     its own, (b) as one chain sharing an arena, launched kernel by kernel, (c) as the chain's captured HIP graph."""
@@ -336,6 +364,7 @@ def main():
         # preparation-execution decoupling over a chain of layers (the launch-bound batch-1 regime and batch 32)
         # kernels with a single row or column (factorised 7-tap layers): planner's choice next to the sliding window
         out["rectangular_kernels"] = run_rect(16, stream, mnn, torch)
+        out["strassen"] = run_strassen(mnn, torch)
         out["chained_execution"] = [run_chain("resnet18_trunk", b, 200 if b == 1 else 50, 10, stream, mnn, torch)
                                     for b in (1, 32)]
     if args.plan_file:

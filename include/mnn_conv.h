@@ -72,7 +72,8 @@ typedef struct {
     float   est_ms;           /* time measured by the planner; < 0 when it was not timed  */
 } mnn_scheme;
 
-/* Kernel arrangements of a Winograd scheme (all compute the same F(n,k)). */
+/* Kernel arrangements of a Winograd scheme (all compute the same F(n,k)).  For MNN_SCHEME_GEMM1X1 the variant
+ * field of mnn_scheme (and force_variant) is the number of Strassen levels, 0..2 (Section 3.3.2). */
 enum {
     MNN_WINO_UNFUSED = 0,     /* input transform, batched GEMM writing M, output transform        */
     MNN_WINO_FUSED_OUT_32 = 1,/* input transform, GEMM with the output transform in its epilogue,
@@ -252,6 +253,28 @@ typedef struct {
 int mnn_gemm_f32(const mnn_gemm_desc* desc, const float* At, const float* B, const float* bias, float* D,
                  void* stream);
 int mnn_gemm_variant_count(int32_t prec);
+
+/*
+ * Strassen's algorithm for one large product (Section 3.3.2), same operand layout as mnn_gemm_f32 with
+ * batch = 1 and prec = MNN_GEMM_FP32.  `levels` recursion levels, each: the 4 + 4 additions on the operand
+ * quadrants, 7 half-size products, 7 additions on the results (the count the paper gives); level l multiplies
+ * 7^l blocks in one batched GEMM.  levels = 0 is the plain GEMM.  levels > 0 needs M and ncols divisible by
+ * 4 * 2^levels, R by 2^levels, and L, lda and all strides divisible by 4 (else MNN_E_UNSUPPORTED).
+ * mnn_strassen_levels_by_rule (host): how many levels, at most max_levels, the paper's rule allows --
+ *   m n k - 7 (m/2)(n/2)(k/2) > 4 (m/2)(k/2) + 4 (n/2)(k/2) + 7 (m/2)(n/2)  for [n,k] x [k,m] at every level --
+ *   under those divisibility conditions.
+ * mnn_strassen_create allocates all temporaries and times the tile configuration of the leaf GEMM on `stream`.
+ * mnn_strassen_set_left expands the left operand At (device, 16-byte aligned; the weights in the convolution
+ * use) once; mnn_strassen_run multiplies it with B (device) into D (device, + bias[m] if bias != NULL),
+ * enqueuing 2*levels + 1 kernels.  At must stay valid while the handle is used with levels = 0.
+ */
+typedef struct mnn_strassen_s* mnn_strassen_t;
+int mnn_strassen_levels_by_rule(int32_t M, int32_t R, int32_t ncols, int32_t max_levels);
+int mnn_strassen_create(const mnn_gemm_desc* desc, int32_t levels, void* stream, mnn_strassen_t* out);
+int mnn_strassen_set_left(mnn_strassen_t h, const float* At, void* stream);
+int mnn_strassen_run(mnn_strassen_t h, const float* B, const float* bias, float* D, void* stream);
+int mnn_strassen_info(mnn_strassen_t h, int32_t* levels, int32_t* launches, size_t* workspace_bytes);
+void mnn_strassen_destroy(mnn_strassen_t h);
 const char* mnn_gemm_variant_name(int32_t prec, int32_t variant);
 
 /*

@@ -119,6 +119,13 @@ def _load() -> ctypes.CDLL:
     L.mnn_chain_destroy.restype = None
     L.mnn_arena_plan.argtypes = [POINTER(ctypes.c_int64), POINTER(c_int32), POINTER(c_int32), c_int32, ctypes.c_int64,
                                  POINTER(ctypes.c_int64), POINTER(ctypes.c_int64)]
+    L.mnn_strassen_levels_by_rule.argtypes = [c_int32] * 4
+    L.mnn_strassen_create.argtypes = [POINTER(_GemmDesc), c_int32, vp, POINTER(vp)]
+    L.mnn_strassen_set_left.argtypes = [vp, vp, vp]
+    L.mnn_strassen_run.argtypes = [vp, vp, vp, vp, vp]
+    L.mnn_strassen_info.argtypes = [vp, POINTER(c_int32), POINTER(c_int32), POINTER(c_size_t)]
+    L.mnn_strassen_destroy.argtypes = [vp]
+    L.mnn_strassen_destroy.restype = None
     L.mnn_conv_cache_size.argtypes = []
     L.mnn_conv_cache_clear.argtypes = []
     L.mnn_conv_cache_clear.restype = None
@@ -158,7 +165,8 @@ class Scheme:
         if self.kind == SCHEME_WINOGRAD:
             v = {WINO_UNFUSED: "", WINO_FUSED_OUT_32: "+fo32", WINO_FUSED_OUT_64: "+fo64"}.get(self.variant, f"+v{self.variant}")
             return f"F({self.tile_n},{k if k is not None else 'k'}){v}{p}"
-        return _KIND_NAMES.get(self.kind, str(self.kind)) + p
+        st = f"+strassen{self.variant}" if (self.kind == SCHEME_GEMM1X1 and self.variant > 0) else ""
+        return _KIND_NAMES.get(self.kind, str(self.kind)) + st + p
 
     def _c(self) -> _Scheme:
         return _Scheme(self.kind, self.tile_n, self.prec, self.variant, self.est_ms)
@@ -258,6 +266,56 @@ def gemm_f32(At, B, D, bias=None, *, M, ncols, R, batch=1, lda=None, L=None, var
     _check(lib.mnn_gemm_f32(byref(d), At.data_ptr(), B.data_ptr(), bias.data_ptr() if bias is not None else None,
                             D.data_ptr(), _stream_handle(stream)))
     return D
+
+
+def strassen_levels_by_rule(M: int, R: int, ncols: int, max_levels: int) -> int:
+    return int(lib.mnn_strassen_levels_by_rule(M, R, ncols, max_levels))
+
+
+class StrassenGemm:
+    """mnn_strassen_*: D[m][col] = sum_r At[r][m] B[r][col] (+ bias[m]) with `levels` levels of Strassen."""
+
+    def __init__(self, M, ncols, R, levels, *, lda=None, L=None, strideB_img=0, strideB_row=None, strideD_img=0,
+                 strideD_row=None, stream=None):
+        self._h = c_void_p()
+        L = ncols if L is None else L
+        d = _GemmDesc(M, ncols, R, 1, M if lda is None else lda, L, 0, GEMM_FP32, 0, 0, strideB_img,
+                      L if strideB_row is None else strideB_row, 0, strideD_img, L if strideD_row is None else strideD_row)
+        _check(lib.mnn_strassen_create(byref(d), levels, _stream_handle(stream), byref(self._h)))
+        self._keep = None
+
+    @property
+    def info(self) -> dict:
+        lv, la, wb = c_int32(), c_int32(), c_size_t()
+        _check(lib.mnn_strassen_info(self._h, byref(lv), byref(la), byref(wb)))
+        return {"levels": lv.value, "launches": la.value, "workspace_bytes": int(wb.value)}
+
+    def set_left(self, At, stream=None):
+        _check(lib.mnn_strassen_set_left(self._h, At.data_ptr(), _stream_handle(stream)))
+        self._keep = At
+
+    def run(self, B, D, bias=None, stream=None):
+        _check(lib.mnn_strassen_run(self._h, B.data_ptr(), bias.data_ptr() if bias is not None else None, D.data_ptr(),
+                                    _stream_handle(stream)))
+        return D
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            lib.mnn_strassen_destroy(self._h)
+            self._h = c_void_p()
+        self._keep = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
 
 
 def cache_size() -> int:

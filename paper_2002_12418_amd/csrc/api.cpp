@@ -151,6 +151,25 @@ void push_wino_variants(std::vector<mnn_scheme>* out, int n, int k, int prec)
         if (wino_variant_available(n, k, v)) out->push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, prec, v));
 }
 
+// Recursion rule of Section 3.3.2 for [n,k] x [k,m]: go one level down while the multiplications saved exceed
+// the additions added,  mnk - 7 (m/2)(n/2)(k/2) > 4 (m/2)(k/2) + 4 (n/2)(k/2) + 7 (m/2)(n/2)  -- compared
+// in eighths to stay in integers -- and, here, while the halves keep the 16-byte granularity of the kernels.
+bool strassen_rule(long long n, long long k, long long m)
+{
+    return 8 * m * n * k - 7 * m * n * k > 8 * (m * k + n * k) + 14 * m * n;
+}
+
+int strassen_levels(int M, int R, int N, int max_levels)
+{
+    int l = 0;
+    long long m = M, r = R, n = N;
+    while (l < max_levels && m % 8 == 0 && n % 8 == 0 && r % 2 == 0 && strassen_rule(m, r, n)) {
+        m /= 2; r /= 2; n /= 2;
+        ++l;
+    }
+    return l;
+}
+
 // Section 3.2 (1): k = 1 -> matrix multiplication; k > 1 -> sliding window or F(n,k).
 std::vector<mnn_scheme> enumerate(const Layer& L, const mnn_conv_options& o)
 {
@@ -161,7 +180,15 @@ std::vector<mnn_scheme> enumerate(const Layer& L, const mnn_conv_options& o)
         out.push_back(make_scheme(base, 0, MNN_GEMM_BF16X3));
         out.push_back(make_scheme(base, 0, MNN_GEMM_BF16));
     }
-    if (is_pointwise(L)) return out;
+    if (is_pointwise(L)) {
+        // Section 3.3.2: the large matrix multiplication with 1 or 2 levels of Strassen, where the paper's rule
+        // says the recursion pays and the halves keep 16-byte rows; variant = number of levels
+        const long long cols = (long long)L.s.n * L.s.h * L.s.w;
+        for (int lv = 1; lv <= 2 && cols < (1ll << 31); ++lv)
+            if (strassen_levels(L.s.c_out, L.s.c_in, (int)cols, lv) == lv && L.s.c_out % 4 == 0 && (L.s.h * L.s.w) % 4 == 0)
+                out.push_back(make_scheme(MNN_SCHEME_GEMM1X1, 0, MNN_GEMM_FP32, lv));
+        return out;
+    }
     if (winograd_admissible(L)) {
         const int k = wino_k(L);
         for (int n = 2; n + k - 1 <= o.alpha_max; ++n) {
@@ -327,6 +354,165 @@ int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
     return MNN_OK;
 }
 
+// ------------------------------------------------------------------ Strassen (Section 3.3.2)
+struct Strassen {
+    GemmProblem top{};                    // the caller's problem (pointers filled per call), batch 1
+    int levels = 0;
+    std::vector<float*> Ax, Bx, Px;       // index l = 1..levels: [7^l][R_l][M_l], [7^l][R_l][N_l], [7^l][M_l][N_l]
+    GemmChoice choice{0, 1};
+    float* sk_partial = nullptr;
+    size_t bytes = 0;
+    bool left_set = false;
+
+    ~Strassen()
+    {
+        for (float* q : Ax) if (q) (void)hipFree(q);
+        for (float* q : Bx) if (q) (void)hipFree(q);
+        for (float* q : Px) if (q) (void)hipFree(q);
+        if (sk_partial) (void)hipFree(sk_partial);
+    }
+
+    static long long pow7(int l) { long long v = 1; while (l-- > 0) v *= 7; return v; }
+    int Ml(int l) const { return top.M >> l; }
+    int Rl(int l) const { return top.R >> l; }
+    int Nl(int l) const { return top.Ncols >> l; }
+
+    GemmProblem leaf_problem() const
+    {
+        const int L = levels;
+        GemmProblem p{};
+        p.At = Ax[L]; p.B = Bx[L]; p.D = Px[L]; p.bias = nullptr;
+        p.M = Ml(L); p.Ncols = Nl(L); p.R = Rl(L); p.batch = (int)pow7(L);
+        p.lda = Ml(L); p.L = Nl(L);
+        p.strideA_batch = (long long)Rl(L) * Ml(L);
+        p.strideB_batch = (long long)Rl(L) * Nl(L); p.strideB_img = 0; p.strideB_row = Nl(L);
+        p.strideD_batch = (long long)Ml(L) * Nl(L); p.strideD_img = 0; p.strideD_row = Nl(L);
+        p.variant = choice.variant; p.prec = top.prec;
+        p.splitk = choice.splitk > 1 ? choice.splitk : 1;
+        p.splitk_partial = sk_partial;
+        return p;
+    }
+
+    int init(const GemmProblem& problem, int want_levels, hipStream_t s)
+    {
+        top = problem;
+        if (top.batch != 1) return fail(MNN_E_INVALID_ARG, "Strassen takes one matrix product (batch 1)");
+        if (want_levels < 0 || want_levels > 4) return fail(MNN_E_INVALID_ARG, "levels must be 0..4");
+        if (want_levels > 0) {
+            const int div = 4 << want_levels;
+            if (top.M % div || top.Ncols % div || top.R % (1 << want_levels))
+                return fail(MNN_E_UNSUPPORTED, "%d Strassen levels need M and ncols divisible by %d and R by %d", want_levels, div,
+                            1 << want_levels);
+            if (top.L % 4 || top.lda % 4 || top.strideB_img % 4 || top.strideB_row % 4 || top.strideD_img % 4 || top.strideD_row % 4)
+                return fail(MNN_E_UNSUPPORTED, "Strassen needs L, lda and all strides divisible by 4");
+            if (pow7(want_levels) * top.M >= (1ll << 31)) return fail(MNN_E_UNSUPPORTED, "too many sub-products");
+        }
+        levels = want_levels;
+        Ax.assign(levels + 1, nullptr); Bx.assign(levels + 1, nullptr); Px.assign(levels + 1, nullptr);
+        hipError_t e;
+        for (int l = 1; l <= levels; ++l) {
+            const size_t nb = (size_t)pow7(l);
+            const size_t ab = nb * Rl(l) * Ml(l) * sizeof(float), bb = nb * Rl(l) * Nl(l) * sizeof(float),
+                         pb = nb * Ml(l) * Nl(l) * sizeof(float);
+            if ((e = hipMalloc((void**)&Ax[l], ab)) != hipSuccess || (e = hipMalloc((void**)&Bx[l], bb)) != hipSuccess ||
+                (e = hipMalloc((void**)&Px[l], pb)) != hipSuccess)
+                return fail_hip(e, "hipMalloc Strassen operands");
+            bytes += ab + bb + pb;
+        }
+        if (levels == 0) {
+            // the plain product: tile configuration by timing on scratch operands of the caller's extents
+            const long long imgs = (top.Ncols + top.L - 1) / top.L;
+            const size_t ab = (size_t)top.R * top.lda * sizeof(float);
+            const size_t bb = (size_t)((imgs - 1) * top.strideB_img + (long long)(top.R - 1) * top.strideB_row + top.L) * sizeof(float);
+            const size_t db = (size_t)((imgs - 1) * top.strideD_img + (long long)(top.M - 1) * top.strideD_row + top.L) * sizeof(float);
+            float *ta = nullptr, *tb = nullptr, *td = nullptr;
+            int rc = MNN_OK;
+            if ((e = hipMalloc((void**)&ta, ab)) != hipSuccess || (e = hipMalloc((void**)&tb, bb)) != hipSuccess ||
+                (e = hipMalloc((void**)&td, db)) != hipSuccess || (e = hipMemset(ta, 0, ab)) != hipSuccess ||
+                (e = hipMemset(tb, 0, bb)) != hipSuccess)
+                rc = fail_hip(e, "Strassen tuning scratch");
+            if (!rc) {
+                GemmProblem p = top;
+                p.At = ta; p.B = tb; p.D = td; p.bias = nullptr; p.variant = 0; p.splitk = 1; p.splitk_partial = nullptr;
+                rc = tune_gemm(p, s, &choice);
+                if (!rc && choice.splitk > 1) {
+                    const size_t pb = (size_t)gemm_splitk_workspace(p, choice.splitk) * sizeof(float);
+                    if ((e = hipMalloc((void**)&sk_partial, pb)) != hipSuccess) rc = fail_hip(e, "hipMalloc split-K partials");
+                    bytes += pb;
+                }
+            }
+            if (ta) (void)hipFree(ta);
+            if (tb) (void)hipFree(tb);
+            if (td) (void)hipFree(td);
+            if (rc) return rc;
+            top.variant = choice.variant;
+            top.splitk = choice.splitk > 1 ? choice.splitk : 1;
+            top.splitk_partial = sk_partial;
+        }
+        if (levels > 0) {
+            // tile configuration of the one batched GEMM at the bottom, by timing like any other shape
+            GemmProblem p = leaf_problem();
+            p.variant = 0; p.splitk = 1; p.splitk_partial = nullptr;
+            int rc = tune_gemm(p, s, &choice);
+            if (rc) return rc;
+            if (choice.splitk > 1) {
+                const size_t pb = (size_t)gemm_splitk_workspace(p, choice.splitk) * sizeof(float);
+                if ((e = hipMalloc((void**)&sk_partial, pb)) != hipSuccess) return fail_hip(e, "hipMalloc split-K partials");
+                bytes += pb;
+            }
+        }
+        return MNN_OK;
+    }
+
+    // expands the left operand (weights) for all levels; once per weight set
+    int set_left(const float* At, hipStream_t s)
+    {
+        if (!At) return fail(MNN_E_INVALID_ARG, "At is NULL");
+        top.At = At;
+        hipError_t e = hipSuccess;
+        for (int l = 1; l <= levels && e == hipSuccess; ++l) {
+            const StrassenView v = (l == 1) ? StrassenView{top.lda, 0, top.lda} : StrassenView{Ml(l - 1), 0, Ml(l - 1)};
+            const float* src = (l == 1) ? At : Ax[l - 1];
+            const long long sb = (l == 1) ? 0 : (long long)Rl(l - 1) * Ml(l - 1);
+            e = launch_strassen_expand(true, v, src, sb, Rl(l), Ml(l), (int)pow7(l - 1), Ax[l], s);
+        }
+        if (e != hipSuccess) return fail_hip(e, "Strassen left expansion");
+        left_set = true;
+        return MNN_OK;
+    }
+
+    int run(const float* B, const float* bias, float* D, hipStream_t s)
+    {
+        if (!B || !D) return fail(MNN_E_INVALID_ARG, "B and D must not be NULL");
+        if (!left_set) return fail(MNN_E_INVALID_ARG, "the left operand has not been set");
+        hipError_t e = hipSuccess;
+        if (levels == 0) {
+            GemmProblem p = top;
+            p.B = B; p.D = D; p.bias = bias;
+            e = launch_gemm_f32(p, s);
+            if (e != hipSuccess) return fail_hip(e, "gemm launch");
+            return MNN_OK;
+        }
+        for (int l = 1; l <= levels && e == hipSuccess; ++l) {
+            const StrassenView v = (l == 1) ? StrassenView{top.L, top.strideB_img, top.strideB_row} : StrassenView{Nl(l - 1), 0, Nl(l - 1)};
+            const float* src = (l == 1) ? B : Bx[l - 1];
+            const long long sb = (l == 1) ? 0 : (long long)Rl(l - 1) * Nl(l - 1);
+            e = launch_strassen_expand(false, v, src, sb, Rl(l), Nl(l), (int)pow7(l - 1), Bx[l], s);
+        }
+        if (e == hipSuccess) e = launch_gemm_f32(leaf_problem(), s);
+        for (int l = levels; l >= 1 && e == hipSuccess; --l) {
+            const StrassenView v = (l == 1) ? StrassenView{top.L, top.strideD_img, top.strideD_row} : StrassenView{Nl(l - 1), 0, Nl(l - 1)};
+            float* dst = (l == 1) ? D : Px[l - 1];
+            const long long db = (l == 1) ? 0 : (long long)Ml(l - 1) * Nl(l - 1);
+            e = launch_strassen_combine(v, Px[l], Ml(l), Nl(l), (int)pow7(l - 1), dst, db, l == 1 ? bias : nullptr, s);
+        }
+        if (e != hipSuccess) return fail_hip(e, "Strassen launch");
+        return MNN_OK;
+    }
+
+    int launches() const { return 2 * levels + 1 + (choice.splitk > 1 ? 1 : 0); }
+};
+
 // ------------------------------------------------------------------ one realised scheme
 struct Impl {
     mnn_scheme scheme{};
@@ -334,6 +520,7 @@ struct Impl {
     WinogradMatrices mats;      // along H (both axes of a square kernel)
     WinogradMatrices mats_w;    // along W (kernels with one row or column; the untransformed axis holds 1 x 1 identities)
     bool rect = false;
+    std::unique_ptr<Strassen> strassen;   // 1x1 scheme with scheme.variant = Strassen levels > 0
     WinoGeom wg{};
     float* U = nullptr; size_t U_bytes = 0;
     float* V = nullptr; size_t V_bytes = 0;
@@ -550,6 +737,13 @@ struct Impl {
             int rc = tune_gemm(p, s, &c);
             return rc ? rc : adopt(p, c);
         }
+        if (scheme.kind == MNN_SCHEME_GEMM1X1 && scheme.variant > 0) {
+            if (scheme.prec != MNN_GEMM_FP32) return fail(MNN_E_UNSUPPORTED, "Strassen runs on the fp32 GEMM only");
+            strassen.reset(new Strassen());
+            GemmProblem p = pointwise_gemm_problem(nullptr, nullptr, nullptr);
+            p.variant = 0; p.splitk = 1; p.splitk_partial = nullptr;
+            return strassen->init(p, scheme.variant, s);
+        }
         if (scheme.kind == MNN_SCHEME_GEMM1X1 || scheme.kind == MNN_SCHEME_DIRECT) {
             const mnn_conv_shape& sh = L.s;
             const size_t xb = (size_t)sh.n * sh.c_in * sh.h * sh.w * sizeof(float);
@@ -619,6 +813,12 @@ struct Impl {
             const int HW = sh.h * sh.w;
             if (st == MNN_STAGE_FILTER) {
                 e = launch_weight_transpose(w, U, sh.c_out, sh.c_in, ldk, s);
+                if (e == hipSuccess && strassen) {
+                    int rc = strassen->set_left(U, s);
+                    if (rc) return rc;
+                }
+            } else if (strassen) {
+                return strassen->run(x, b, y, s);
             } else {
                 e = launch_gemm_f32(pointwise_gemm_problem(x, b, y), s);
             }
@@ -632,7 +832,7 @@ struct Impl {
         return MNN_OK;
     }
 
-    size_t bytes() const { return U_bytes + V_bytes + M_bytes + sk_partial_bytes; }
+    size_t bytes() const { return U_bytes + V_bytes + M_bytes + sk_partial_bytes + (strassen ? strassen->bytes : 0); }
 };
 
 void describe_impl(const Impl& im, char* buf, size_t cap)
@@ -650,7 +850,14 @@ void describe_impl(const Impl& im, char* buf, size_t cap)
                 std::snprintf(buf, cap, "F(%d,%d) fused-output %s", im.wg.n, im.wg.k,
                               im.scheme.variant == MNN_WINO_FUSED_OUT_32 ? "32x32" : "64x64");
             break;
-        case MNN_SCHEME_GEMM1X1: std::snprintf(buf, cap, "gemm1x1 gemm=%s", gv); break;
+        case MNN_SCHEME_GEMM1X1:
+            if (im.strassen) {
+                const char* leaf = gemm_variant_name(MNN_GEMM_FP32, im.strassen->choice.variant);
+                std::snprintf(buf, cap, "gemm1x1 strassen levels=%d gemm=%s", im.strassen->levels, leaf ? leaf : "?");
+            } else {
+                std::snprintf(buf, cap, "gemm1x1 gemm=%s", gv);
+            }
+            break;
         default: std::snprintf(buf, cap, "sliding-window implicit gemm=%s", gv); break;
     }
 }
@@ -714,7 +921,9 @@ struct mnn_chain_s {
         int k = 0;
         for (const auto& im : impls)
             for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st)
-                if (im->has_stage(st)) k += (st == MNN_STAGE_GEMM && im->gemm_splitk > 1) ? 2 : 1;   // + the slice reduction
+                if (im->has_stage(st))
+                    k += (st == MNN_STAGE_GEMM && im->strassen) ? im->strassen->launches()
+                         : (st == MNN_STAGE_GEMM && im->gemm_splitk > 1) ? 2 : 1;                // + the slice reduction
         return k;
     }
 
@@ -829,7 +1038,8 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
                 push_wino_variants(&plan->cands, n, L.s.kh, o.force_prec);   // time the arrangements of this F(n,k)
             if (plan->cands.empty()) plan->cands.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, o.force_prec, 0));
         } else {
-            plan->cands.push_back(make_scheme(o.force_kind, 0, o.force_prec));
+            const int lv = (o.force_kind == MNN_SCHEME_GEMM1X1 && o.force_variant > 0) ? o.force_variant : 0;   // Strassen levels
+            plan->cands.push_back(make_scheme(o.force_kind, 0, o.force_prec, lv));
         }
     } else {
         plan->cands = enumerate(L, o);
@@ -1135,6 +1345,69 @@ int mnn_gemm_f32(const mnn_gemm_desc* d, const float* At, const float* B, const 
     if (e != hipSuccess) return fail_hip(e, "gemm launch");
     return MNN_OK;
 }
+
+struct mnn_strassen_s { Strassen impl; };
+
+int mnn_strassen_levels_by_rule(int32_t M, int32_t R, int32_t ncols, int32_t max_levels)
+{
+    if (M <= 0 || R <= 0 || ncols <= 0 || max_levels < 0) return 0;
+    return strassen_levels(M, R, ncols, max_levels);
+}
+
+int mnn_strassen_create(const mnn_gemm_desc* d, int32_t levels, void* stream, mnn_strassen_t* out)
+{
+    if (!d || !out) return fail(MNN_E_INVALID_ARG, "NULL argument");
+    *out = nullptr;
+    if (d->M <= 0 || d->ncols <= 0 || d->R <= 0 || d->L <= 0 || d->lda < d->M) return fail(MNN_E_INVALID_ARG, "bad GEMM descriptor");
+    if (d->prec != MNN_GEMM_FP32) return fail(MNN_E_UNSUPPORTED, "Strassen runs on the fp32 GEMM only");
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        return fail(MNN_E_NO_DEVICE, "no HIP device available");
+    }
+    GemmProblem p{};
+    p.M = d->M; p.Ncols = d->ncols; p.R = d->R; p.batch = d->batch; p.lda = d->lda; p.L = d->L;
+    p.variant = d->variant; p.prec = d->prec;
+    p.strideA_batch = d->strideA_batch;
+    p.strideB_batch = d->strideB_batch; p.strideB_img = d->strideB_img; p.strideB_row = d->strideB_row;
+    p.strideD_batch = d->strideD_batch; p.strideD_img = d->strideD_img; p.strideD_row = d->strideD_row;
+    mnn_strassen_s* h = new (std::nothrow) mnn_strassen_s();
+    if (!h) return fail(MNN_E_OOM, "host allocation failed");
+    int rc;
+    try {
+        rc = h->impl.init(p, levels, (hipStream_t)stream);
+    } catch (const std::bad_alloc&) {
+        rc = fail(MNN_E_OOM, "host allocation failed");
+    }
+    if (rc) { delete h; return rc; }
+    *out = h;
+    return MNN_OK;
+}
+
+int mnn_strassen_set_left(mnn_strassen_t h, const float* At, void* stream)
+{
+    if (!h) return fail(MNN_E_INVALID_ARG, "handle is NULL");
+    if (At && (reinterpret_cast<uintptr_t>(At) & 15u)) return fail(MNN_E_INVALID_ARG, "At must be 16-byte aligned");
+    return h->impl.set_left(At, (hipStream_t)stream);
+}
+
+int mnn_strassen_run(mnn_strassen_t h, const float* B, const float* bias, float* D, void* stream)
+{
+    if (!h) return fail(MNN_E_INVALID_ARG, "handle is NULL");
+    return h->impl.run(B, bias, D, (hipStream_t)stream);
+}
+
+int mnn_strassen_info(mnn_strassen_t h, int32_t* levels, int32_t* launches, size_t* workspace_bytes)
+{
+    if (!h) return fail(MNN_E_INVALID_ARG, "handle is NULL");
+    if (levels) *levels = h->impl.levels;
+    if (launches) *launches = h->impl.launches();
+    if (workspace_bytes) *workspace_bytes = h->impl.bytes;
+    return MNN_OK;
+}
+
+void mnn_strassen_destroy(mnn_strassen_t h) { delete h; }
 
 int mnn_gemm_variant_count(int32_t prec)
 {

@@ -116,6 +116,19 @@ bool gemm_bf16_variant_tile(int variant, int* bm, int* bn, int* bk);
 inline int gemm_variant_count(int prec) { return prec == 0 ? gemm_f32_variant_count() : gemm_bf16_variant_count(); }
 inline const char* gemm_variant_name(int prec, int v) { return prec == 0 ? gemm_f32_variant_name(v) : gemm_bf16_variant_name(v); }
 
+// Strassen's algorithm (Section 3.3.2), one level = expand both operands, one batched GEMM, combine.
+// A view addresses element (r, c) of a row-major operand at  (c / L) * sImg + r * sRow + c % L  (the column
+// mapping of the GEMM: L consecutive columns are contiguous, the next L belong to the next image).
+// All of L, sImg, sRow and the half widths must be multiples of 4, bases 16-byte aligned.
+struct StrassenView { int L; long long sImg, sRow; };
+// src: nb operands [2*rows_half][2*cols_half] (batch stride in floats) -> dst [7*nb][rows_half][cols_half] dense.
+// left: the operand is A stored transposed (At[r][m]); otherwise it is B.
+hipError_t launch_strassen_expand(bool left, const StrassenView& v, const float* src, long long src_batch_stride, int rows_half,
+                                  int cols_half, int nb, float* dst, hipStream_t s);
+// src: [7*nb][rows_half][cols_half] dense products -> dst: nb results [2*rows_half][2*cols_half] (+ bias per row, nb = 1).
+hipError_t launch_strassen_combine(const StrassenView& v, const float* src, int rows_half, int cols_half, int nb, float* dst,
+                                   long long dst_batch_stride, const float* bias, hipStream_t s);
+
 // Wt[r][k] = w[k][r], r < R = C*kh*kw, row length ldk (zero padded)
 hipError_t launch_weight_transpose(const float* w, float* Wt, int K, int R, int ldk, hipStream_t s);
 

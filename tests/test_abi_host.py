@@ -76,7 +76,12 @@ def test_analytic_cost_matches_oracle_model(mnn, shape):
 def test_enumeration_rules(mnn):
     # k = 1, stride 1, no padding -> one matrix multiplication
     c = mnn.enumerate_schemes(16, 32, 112, 112, 64, 1, 1)
-    assert [s.kind for s in c] == [mnn.SCHEME_GEMM1X1]
+    assert all(s.kind == mnn.SCHEME_GEMM1X1 for s in c)
+    assert [s.variant for s in c] == [0, 1]               # plain and one level of Strassen (the rule stops at 32 x 16)
+    c = mnn.enumerate_schemes(16, 256, 14, 14, 512, 1, 1)
+    assert [(s.kind, s.variant) for s in c] == [(mnn.SCHEME_GEMM1X1, v) for v in (0, 1, 2)]
+    c = mnn.enumerate_schemes(3, 19, 7, 7, 21, 1, 1)       # nothing divides: the plain product only
+    assert [(s.kind, s.variant) for s in c] == [(mnn.SCHEME_GEMM1X1, 0)]
     # stride 2 / dilation 2 / a kernel that is neither square nor a single row or column -> sliding window only
     for kw in (dict(stride=2, pad=1), dict(dil=2, pad=2)):
         c = mnn.enumerate_schemes(1, 64, 56, 56, 128, 3, 3, **kw)
@@ -179,7 +184,8 @@ def test_enumeration_with_bf16_allowed(mnn):
     assert sorted(s.tile_n for s in x3) == [0, 2, 3, 4, 5, 6] and all(s.variant == 0 for s in x3)
     assert [(s.kind, s.tile_n) for s in plain] == [(mnn.SCHEME_DIRECT, 0)]
     c = mnn.enumerate_schemes(16, 32, 112, 112, 64, 1, 1, options=mnn.Options(allow_bf16=1))
-    assert [(s.kind, s.prec) for s in c] == [(mnn.SCHEME_GEMM1X1, 0), (mnn.SCHEME_GEMM1X1, 2), (mnn.SCHEME_GEMM1X1, 1)]
+    assert [(s.kind, s.prec, s.variant) for s in c] == [(mnn.SCHEME_GEMM1X1, 0, 0), (mnn.SCHEME_GEMM1X1, 2, 0),
+                                                        (mnn.SCHEME_GEMM1X1, 1, 0), (mnn.SCHEME_GEMM1X1, 0, 1)]
 
 
 def test_product_path_does_not_import_the_oracle():
@@ -215,3 +221,20 @@ def test_cache_file_round_trip_rejects_garbage(mnn, tmp_path):
         mnn.cache_load(str(bad))
     with pytest.raises(mnn.MnnError):
         mnn.cache_load(str(tmp_path / "missing.txt"))
+
+
+def test_strassen_rule_matches_oracle(mnn):
+    """Levels the library allows = the paper's inequality (oracle.cost_model) at every level, cut where the
+    halves would lose 16-byte rows (M, ncols divisible by 8, R by 2 before each halving)."""
+    def expected(M, R, N, cap):
+        lv = 0
+        while lv < cap and M % 8 == 0 and N % 8 == 0 and R % 2 == 0 and cost_model.strassen_should_recurse(M, R, N):
+            M, R, N, lv = M // 2, R // 2, N // 2, lv + 1
+        return lv
+    for shape in [(1024, 1024, 784), (1024, 512, 784), (256, 256, 256), (512, 512, 1024), (64, 32, 200704),
+                  (24, 6, 24), (8, 2, 8), (16, 16, 16), (32, 32, 32), (30, 30, 30), (40, 12, 56), (1024, 1024, 788)]:
+        for cap in (0, 1, 2, 4):
+            assert mnn.strassen_levels_by_rule(shape[0], shape[1], shape[2], cap) == expected(*shape, cap), (shape, cap)
+    # the paper's Table 3 sizes all pass the rule at the first level
+    for n in (256, 512, 1024):
+        assert mnn.strassen_levels_by_rule(n, n, n, 1) == 1
