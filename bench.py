@@ -134,6 +134,12 @@ def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
             entry["analytic_n"] = mnn.analytic_tile(layer.kh, layer.c_in, layer.c_out, layer.h_out, layer.w_out,
                                                     mnn.Options.defaults().alpha_max)
             entry["timed_n"] = sch.tile_n if sch.kind == mnn.SCHEME_WINOGRAD else 1
+            # the same question put to the device cost model (work / FLOPS and bytes / bandwidth + t_schedule per kernel)
+            cands = mnn.enumerate_schemes(layer.n, layer.c_in, layer.h, layer.w, layer.c_out, layer.kh, layer.kw,
+                                          stride=layer.stride, pad=layer.pad, dil=layer.dil)
+            pred = min(cands, key=lambda c: mnn.predict_ms(layer.n, layer.c_in, layer.h, layer.w, layer.c_out, layer.kh,
+                                                           layer.kw, c, stride=layer.stride, pad=layer.pad, dil=layer.dil))
+            entry["model_n"] = pred.tile_n if pred.kind == mnn.SCHEME_WINOGRAD else 1
         lay_ms = sum(ms[1:4])
         entry["ms"] = round(lay_ms, 5)
         entry["gflops_direct_count"] = round(layer.direct_flops / (lay_ms * 1e-3) / 1e9, 1) if lay_ms > 0 else None
@@ -360,7 +366,10 @@ def main():
         # tile size that wins on the clock
         out["analytic_vs_timed"] = {
             "layers": len(compared), "same_n": sum(1 for e in compared if e["analytic_n"] == e["timed_n"]),
-            "detail": {e["layer"] + f"[{i}]": [e["analytic_n"], e["timed_n"]] for i, e in enumerate(compared)}}
+            "device_model": mnn.get_device_model(),
+            "device_model_same_n": sum(1 for e in compared if e["model_n"] == e["timed_n"]),
+            "detail_analytic_model_timed": {e["layer"] + f"[{i}]": [e["analytic_n"], e["model_n"], e["timed_n"]]
+                                            for i, e in enumerate(compared)}}
         # preparation-execution decoupling over a chain of layers (the launch-bound batch-1 regime and batch 32)
         # kernels with a single row or column (factorised 7-tap layers): planner's choice next to the sliding window
         out["rectangular_kernels"] = run_rect(16, stream, mnn, torch)

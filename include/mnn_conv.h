@@ -97,6 +97,8 @@ typedef struct {
     int32_t plan_warmup;      /* untimed launches per candidate (default 2)               */
     int32_t plan_iters;       /* timed launches per candidate (default 10)                */
     int32_t use_cache;        /* 1 (default): consult / fill the process-wide choice cache */
+    float   prune_ratio;      /* > 1: candidates whose predicted time (mnn_conv_predict_ms) exceeds prune_ratio times
+                                 the best predicted one are not timed; 0 (default): time every candidate */
 } mnn_conv_options;
 
 typedef struct mnn_conv_plan_s* mnn_conv_plan_t;
@@ -224,6 +226,26 @@ int mnn_conv_analytic_cost(int32_t k, int32_t i_c, int32_t o_c, int32_t o_h, int
                            int32_t n, double* cost);
 int mnn_conv_analytic_tile(int32_t k, int32_t i_c, int32_t o_c, int32_t o_h, int32_t o_w,
                            int32_t alpha_max, int32_t* n_hat);
+
+/*
+ * Cost of an operator on this device in the form of Section 3.2 (2): work / FLOPS + t_schedule per kernel,
+ * with the memory side added (a kernel takes max(flops / FLOPS, bytes / bandwidth) + t_schedule), summed over
+ * the kernels a scheme launches.  The three constants are "known constants for a specific backend"; the
+ * defaults were measured on an MI355X (fp32 matrix-core rate of the GEMM, rate of the transform kernels,
+ * dispatch-to-dispatch time of dependent kernels); mnn_conv_calibrate re-measures them on `stream` (a large
+ * product, a large copy, a chain of empty kernels; about 50 ms) and installs the result process-wide.
+ * mnn_conv_predict_ms: host only; the predicted milliseconds of `scheme` for the layer.
+ */
+typedef struct {
+    double flops;             /* fp32 multiply-add rate of the matrix-multiplication stage, FLOP/s */
+    double bytes_per_s;       /* sustained HBM rate of a streaming kernel, B/s                     */
+    double t_schedule_ms;     /* fixed cost per kernel launch in a dependent chain, ms             */
+} mnn_device_model;
+int mnn_conv_get_device_model(mnn_device_model* out);
+int mnn_conv_set_device_model(const mnn_device_model* model);
+int mnn_conv_calibrate(void* stream, mnn_device_model* out);
+int mnn_conv_predict_ms(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_scheme* scheme,
+                        double* ms);
 
 /* The candidate list mnn_conv_plan would time for this layer, without touching
  * the device.  Host only.  Same cap / count convention as above. */

@@ -46,7 +46,11 @@ class _Scheme(ctypes.Structure):
 class _Options(ctypes.Structure):
     _fields_ = [("force_kind", c_int32), ("force_tile_n", c_int32), ("force_prec", c_int32),
                 ("force_variant", c_int32), ("allow_bf16", c_int32), ("alpha_max", c_int32), ("point_scale_f", c_float),
-                ("plan_warmup", c_int32), ("plan_iters", c_int32), ("use_cache", c_int32)]
+                ("plan_warmup", c_int32), ("plan_iters", c_int32), ("use_cache", c_int32), ("prune_ratio", c_float)]
+
+
+class _DeviceModel(ctypes.Structure):
+    _fields_ = [("flops", c_double), ("bytes_per_s", c_double), ("t_schedule_ms", c_double)]
 
 
 class _GemmDesc(ctypes.Structure):
@@ -126,6 +130,10 @@ def _load() -> ctypes.CDLL:
     L.mnn_strassen_info.argtypes = [vp, POINTER(c_int32), POINTER(c_int32), POINTER(c_size_t)]
     L.mnn_strassen_destroy.argtypes = [vp]
     L.mnn_strassen_destroy.restype = None
+    L.mnn_conv_get_device_model.argtypes = [POINTER(_DeviceModel)]
+    L.mnn_conv_set_device_model.argtypes = [POINTER(_DeviceModel)]
+    L.mnn_conv_calibrate.argtypes = [vp, POINTER(_DeviceModel)]
+    L.mnn_conv_predict_ms.argtypes = [POINTER(_Shape), POINTER(_Geom), POINTER(_Scheme), POINTER(c_double)]
     L.mnn_conv_cache_size.argtypes = []
     L.mnn_conv_cache_clear.argtypes = []
     L.mnn_conv_cache_clear.restype = None
@@ -188,10 +196,11 @@ class Options:
     plan_warmup: int = 2
     plan_iters: int = 10
     use_cache: int = 1
+    prune_ratio: float = 0.0
 
     def _c(self) -> _Options:
         return _Options(self.force_kind, self.force_tile_n, self.force_prec, self.force_variant, self.allow_bf16, self.alpha_max,
-                        self.point_scale_f, self.plan_warmup, self.plan_iters, self.use_cache)
+                        self.point_scale_f, self.plan_warmup, self.plan_iters, self.use_cache, self.prune_ratio)
 
     @staticmethod
     def defaults() -> "Options":
@@ -316,6 +325,31 @@ class StrassenGemm:
 
     def __exit__(self, *exc):
         self.close()
+
+
+def get_device_model() -> dict:
+    m = _DeviceModel()
+    _check(lib.mnn_conv_get_device_model(byref(m)))
+    return {"flops": m.flops, "bytes_per_s": m.bytes_per_s, "t_schedule_ms": m.t_schedule_ms}
+
+
+def set_device_model(flops: float, bytes_per_s: float, t_schedule_ms: float) -> None:
+    m = _DeviceModel(flops, bytes_per_s, t_schedule_ms)
+    _check(lib.mnn_conv_set_device_model(byref(m)))
+
+
+def calibrate(stream=None) -> dict:
+    m = _DeviceModel()
+    _check(lib.mnn_conv_calibrate(_stream_handle(stream), byref(m)))
+    return {"flops": m.flops, "bytes_per_s": m.bytes_per_s, "t_schedule_ms": m.t_schedule_ms}
+
+
+def predict_ms(n, c_in, h, w, c_out, kh, kw, scheme: "Scheme", stride=1, pad=0, dil=1) -> float:
+    s, g = _shape_geom(n, c_in, h, w, c_out, kh, kw, stride, pad, dil)
+    c = scheme._c()
+    ms = c_double()
+    _check(lib.mnn_conv_predict_ms(byref(s), byref(g), byref(c), byref(ms)))
+    return float(ms.value)
 
 
 def cache_size() -> int:

@@ -7,6 +7,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
+#include <cmath>
 #include <map>
 #include <memory>
 #include <mutex>
@@ -59,6 +61,7 @@ void default_options(mnn_conv_options* o)
     o->plan_warmup = 2;
     o->plan_iters = 10;
     o->use_cache = 1;
+    o->prune_ratio = 0.f;
 }
 
 struct Layer {
@@ -105,6 +108,7 @@ int validate_options(const mnn_conv_options* in, mnn_conv_options* o)
         return fail(MNN_E_INVALID_ARG, "unknown force_prec %d", o->force_prec);
     if (o->force_variant < -1 || o->force_variant >= MNN_WINO_VARIANTS)
         return fail(MNN_E_INVALID_ARG, "unknown force_variant %d", o->force_variant);
+    if (!(o->prune_ratio == 0.f || o->prune_ratio > 1.f)) return fail(MNN_E_INVALID_ARG, "prune_ratio must be 0 or above 1");
     return MNN_OK;
 }
 
@@ -223,6 +227,65 @@ int analytic_tile(int k, int ic, int oc, int oh, int ow, int alpha_max)
         if (c < bc) { bc = c; best = n; }
     }
     return best;
+}
+
+// ------------------------------------------------------------------ device cost model (Section 3.2 (2))
+// C_op = work / FLOPS + t_schedule per kernel, with the memory side added.  Defaults: measured on MI355X.
+std::mutex g_model_mu;
+mnn_device_model g_model = {115e12, 4.4e12, 0.005};
+
+struct KernelWork { double flops, bytes; };
+
+// the kernels one inference of `s` launches for layer L, with their algorithmic work
+std::vector<KernelWork> scheme_kernels(const Layer& L, const mnn_scheme& s)
+{
+    const double N = L.s.n, C = L.s.c_in, K = L.s.c_out, H = L.s.h, W = L.s.w, Ho = L.Ho, Wo = L.Wo;
+    const double in_b = 4.0 * N * C * H * W, out_b = 4.0 * N * K * Ho * Wo, w_b = 4.0 * K * C * L.s.kh * L.s.kw;
+    std::vector<KernelWork> v;
+    if (s.kind == MNN_SCHEME_WINOGRAD) {
+        const bool rect = winograd_rect(L);
+        const double n = s.tile_n, k = wino_k(L), a = n + k - 1;
+        const double nh = (rect && L.s.kh == 1) ? 1 : n, nw = (rect && L.s.kw == 1) ? 1 : n;
+        const double ah = (rect && L.s.kh == 1) ? 1 : a, aw = (rect && L.s.kw == 1) ? 1 : a;
+        const double P = N * std::ceil(Ho / nh) * std::ceil(Wo / nw), a2 = ah * aw;
+        v.push_back(KernelWork{2.0 * (ah * ah * aw + ah * aw * aw) * C * P, in_b + 4.0 * a2 * C * P});
+        if (s.variant == MNN_WINO_UNFUSED) {
+            v.push_back(KernelWork{2.0 * a2 * K * C * P, 4.0 * a2 * (K * C + C * P + K * P)});
+            v.push_back(KernelWork{2.0 * (nh * ah * aw + nh * nw * aw) * K * P, 4.0 * a2 * K * P + out_b});
+        } else {
+            v.push_back(KernelWork{2.0 * a2 * K * C * P, 4.0 * a2 * (K * C + C * P) + out_b});
+        }
+        return v;
+    }
+    const double direct = 2.0 * N * K * C * Ho * Wo * L.s.kh * L.s.kw;
+    if (s.kind == MNN_SCHEME_GEMM1X1 && s.variant > 0) {
+        // Strassen: per level an expand and a combine pass over 7/4 of the operands, 7/8 of the products
+        double flops = direct, bb = in_b, pb = out_b;
+        for (int l = 0; l < s.variant; ++l) {
+            v.push_back(KernelWork{0.0, bb + 1.75 * bb});
+            v.push_back(KernelWork{0.0, 1.75 * pb + pb});
+            flops *= 0.875; bb *= 1.75; pb *= 1.75;
+        }
+        v.push_back(KernelWork{flops, bb + pb + w_b});
+        return v;
+    }
+    v.push_back(KernelWork{direct, in_b + out_b + w_b});
+    return v;
+}
+
+double predict_ms(const Layer& L, const mnn_scheme& s)
+{
+    mnn_device_model m;
+    {
+        std::lock_guard<std::mutex> lk(g_model_mu);
+        m = g_model;
+    }
+    // bf16x3 runs three bf16 products per fp32 one at 16x the fp32 matrix-core rate; plain bf16 one
+    const double rate = s.prec == MNN_GEMM_BF16X3 ? m.flops * 16.0 / 3.0 : s.prec == MNN_GEMM_BF16 ? m.flops * 16.0 : m.flops;
+    double ms = 0.0;
+    for (const KernelWork& k : scheme_kernels(L, s))
+        ms += std::max(k.flops / rate, k.bytes / m.bytes_per_s) * 1e3 + m.t_schedule_ms;
+    return ms;
 }
 
 int select_scheme(const mnn_scheme* c, int count, int k)
@@ -871,7 +934,7 @@ CacheKey cache_key(int device, const Layer& L, const mnn_conv_options& o)
 {
     std::vector<int> v = {L.s.n, L.s.c_in, L.s.h, L.s.w, L.s.c_out, L.s.kh, L.s.kw,
                           L.g.stride_h, L.g.stride_w, L.g.pad_h, L.g.pad_w, L.g.dil_h, L.g.dil_w,
-                          o.alpha_max, o.allow_bf16};
+                          o.alpha_max, o.allow_bf16, (int)std::lround((double)o.prune_ratio * 1000.0)};
     return CacheKey(device, v, o.point_scale_f);
 }
 
@@ -1070,7 +1133,13 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
                     delete plan;
                     return fail_hip(e, "hipMemset planner scratch");
                 }
+                double best_pred = -1.0;
+                for (const auto& c : plan->cands) {
+                    const double pm = predict_ms(L, c);
+                    if (best_pred < 0.0 || pm < best_pred) best_pred = pm;
+                }
                 for (auto& c : plan->cands) {
+                    if (o.prune_ratio > 1.f && predict_ms(L, c) > (double)o.prune_ratio * best_pred) { c.est_ms = -1.f; continue; }
                     rc = time_candidate(L, o, &c, sc, s);
                     if (rc == MNN_E_OOM) { c.est_ms = -1.f; (void)hipGetLastError(); continue; }   // does not fit: not a candidate
                     if (rc) { delete plan; return rc; }
@@ -1419,6 +1488,97 @@ const char* mnn_gemm_variant_name(int32_t prec, int32_t variant)
     return (prec < MNN_GEMM_FP32 || prec > MNN_GEMM_BF16X3) ? nullptr : gemm_variant_name(prec, variant);
 }
 
+int mnn_conv_get_device_model(mnn_device_model* out)
+{
+    if (!out) return fail(MNN_E_INVALID_ARG, "out is NULL");
+    std::lock_guard<std::mutex> lk(g_model_mu);
+    *out = g_model;
+    return MNN_OK;
+}
+
+int mnn_conv_set_device_model(const mnn_device_model* m)
+{
+    if (!m || !(m->flops > 0.0) || !(m->bytes_per_s > 0.0) || !(m->t_schedule_ms >= 0.0))
+        return fail(MNN_E_INVALID_ARG, "flops and bytes_per_s must be positive, t_schedule_ms not negative");
+    std::lock_guard<std::mutex> lk(g_model_mu);
+    g_model = *m;
+    return MNN_OK;
+}
+
+int mnn_conv_calibrate(void* stream, mnn_device_model* out)
+{
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        return fail(MNN_E_NO_DEVICE, "no HIP device available");
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const int M = 4096, R = 2048, N = 4096;
+    const size_t copy_bytes = (size_t)256 << 20;
+    float *a = nullptr, *b = nullptr, *d = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = MNN_OK;
+    mnn_device_model m{};
+    do {
+        if ((e = hipMalloc((void**)&a, (size_t)R * M * 4)) != hipSuccess || (e = hipMalloc((void**)&b, copy_bytes)) != hipSuccess ||
+            (e = hipMalloc((void**)&d, copy_bytes)) != hipSuccess || (e = hipMemset(a, 0, (size_t)R * M * 4)) != hipSuccess ||
+            (e = hipMemset(b, 0, copy_bytes)) != hipSuccess || (e = hipEventCreate(&e0)) != hipSuccess ||
+            (e = hipEventCreate(&e1)) != hipSuccess) {
+            rc = fail_hip(e, "calibration set-up");
+            break;
+        }
+        auto timed = [&](int reps, const std::function<hipError_t()>& launch, double* ms_each) -> int {
+            hipError_t er = launch();                                    // warm-up
+            if (er == hipSuccess) er = hipEventRecord(e0, s);
+            for (int i = 0; i < reps && er == hipSuccess; ++i) er = launch();
+            if (er == hipSuccess) er = hipEventRecord(e1, s);
+            if (er == hipSuccess) er = hipEventSynchronize(e1);
+            float ms = 0.f;
+            if (er == hipSuccess) er = hipEventElapsedTime(&ms, e0, e1);
+            if (er != hipSuccess) return fail_hip(er, "calibration run");
+            *ms_each = (double)ms / reps;
+            return MNN_OK;
+        };
+        GemmProblem p{};
+        p.At = a; p.B = b; p.D = d; p.M = M; p.Ncols = N; p.R = R; p.batch = 1; p.lda = M; p.L = N;
+        p.strideB_row = N; p.strideD_row = N;
+        GemmChoice c{0, 1};
+        if ((rc = tune_gemm(p, s, &c))) break;
+        p.variant = c.variant;                                           // 4096 tiles: never split
+        double ms = 0.0;
+        if ((rc = timed(5, [&] { return launch_gemm_f32(p, s); }, &ms))) break;
+        m.flops = 2.0 * M * R * N / (ms * 1e-3);
+        if ((rc = timed(5, [&] { return hipMemcpyAsync(d, b, copy_bytes, hipMemcpyDeviceToDevice, s); }, &ms))) break;
+        m.bytes_per_s = 2.0 * (double)copy_bytes / (ms * 1e-3);
+        if ((rc = timed(200, [&] { return launch_weight_transpose(a, d, 1, 1, 4, s); }, &ms))) break;
+        m.t_schedule_ms = ms;
+    } while (false);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (a) (void)hipFree(a);
+    if (b) (void)hipFree(b);
+    if (d) (void)hipFree(d);
+    if (rc) return rc;
+    if ((rc = mnn_conv_set_device_model(&m))) return rc;
+    if (out) *out = m;
+    return MNN_OK;
+}
+
+int mnn_conv_predict_ms(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_scheme* scheme, double* ms)
+{
+    if (!scheme || !ms) return fail(MNN_E_INVALID_ARG, "NULL argument");
+    Layer L;
+    int rc = validate(shape, geom, &L);
+    if (rc) return rc;
+    if (scheme->kind == MNN_SCHEME_WINOGRAD && (!winograd_admissible(L) || scheme->tile_n < 2))
+        return fail(MNN_E_UNSUPPORTED, "not a Winograd layer or tile");
+    if (scheme->kind == MNN_SCHEME_GEMM1X1 && !is_pointwise(L)) return fail(MNN_E_UNSUPPORTED, "not a 1x1 layer");
+    if (scheme->kind < MNN_SCHEME_DIRECT || scheme->kind > MNN_SCHEME_GEMM1X1) return fail(MNN_E_INVALID_ARG, "unknown scheme kind");
+    *ms = predict_ms(L, *scheme);
+    return MNN_OK;
+}
+
 int mnn_conv_cache_size(void)
 {
     std::lock_guard<std::mutex> lk(g_cache_mu);
@@ -1436,7 +1596,7 @@ int mnn_conv_cache_save(const char* path)
     if (!path) return fail(MNN_E_INVALID_ARG, "path is NULL");
     FILE* f = std::fopen(path, "w");
     if (!f) return fail(MNN_E_INVALID_ARG, "cannot open %s for writing", path);
-    std::fprintf(f, "mnnconv-plan-cache 1\n");
+    std::fprintf(f, "mnnconv-plan-cache 2\n");
     {
         std::lock_guard<std::mutex> lk(g_cache_mu);
         for (const auto& kv : g_cache) {
@@ -1468,7 +1628,7 @@ int mnn_conv_cache_load(const char* path)
     int version = 0;
     int rc = MNN_OK;
     try {
-        if (std::fscanf(f, "mnnconv-plan-cache %d", &version) != 1 || version != 1) {
+        if (std::fscanf(f, "mnnconv-plan-cache %d", &version) != 1 || version != 2) {
             rc = fail(MNN_E_INVALID_ARG, "%s is not a plan cache of this library", path);
         } else {
             char tag[4];

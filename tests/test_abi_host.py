@@ -207,11 +207,11 @@ def test_cache_file_round_trip_rejects_garbage(mnn, tmp_path):
     good = tmp_path / "plans.txt"
     mnn.cache_clear()
     mnn.cache_save(str(good))
-    assert good.read_text().startswith("mnnconv-plan-cache 1")
+    assert good.read_text().startswith("mnnconv-plan-cache 2")
     mnn.cache_load(str(good))
     assert mnn.cache_size() == 0
     # a hand-written entry: device 0, cfg1 layer with the default options, F(4,3) unfused
-    good.write_text("mnnconv-plan-cache 1\nS 0 15 1 16 32 32 16 3 3 1 1 1 1 1 1 8 0 0.5 | 2 4 0 0 0.01\n")
+    good.write_text("mnnconv-plan-cache 2\nS 0 16 1 16 32 32 16 3 3 1 1 1 1 1 1 8 0 0 0.5 | 2 4 0 0 0.01\n")
     mnn.cache_load(str(good))
     assert mnn.cache_size() == 1
     mnn.cache_clear()
@@ -238,3 +238,36 @@ def test_strassen_rule_matches_oracle(mnn):
     # the paper's Table 3 sizes all pass the rule at the first level
     for n in (256, 512, 1024):
         assert mnn.strassen_levels_by_rule(n, n, n, 1) == 1
+
+
+def test_device_cost_model(mnn):
+    """Section 3.2 (2): per kernel work / FLOPS + t_schedule, with the memory side added.  Checked against the
+    formula written out here for an unfused F(4,3) layer and a sliding-window layer, under a model with round
+    numbers; then the default model's constants are restored."""
+    saved = mnn.get_device_model()
+    try:
+        mnn.set_device_model(1e14, 4e12, 0.01)
+        N, C, H, K, k, n = 32, 128, 28, 128, 3, 4
+        a, P = n + k - 1, N * 7 * 7
+        x_b, y_b = 4.0 * N * C * H * H, 4.0 * N * K * H * H
+        kernels = [(2.0 * 2 * a ** 3 * C * P, x_b + 4.0 * a * a * C * P),
+                   (2.0 * a * a * K * C * P, 4.0 * a * a * (K * C + C * P + K * P)),
+                   (2.0 * (n * a * a + n * n * a) * K * P, 4.0 * a * a * K * P + y_b)]
+        want = sum(max(f / 1e14, b / 4e12) * 1e3 + 0.01 for f, b in kernels)
+        got = mnn.predict_ms(N, C, H, H, K, k, k, mnn.Scheme(mnn.SCHEME_WINOGRAD, n, mnn.GEMM_FP32, mnn.WINO_UNFUSED, -1.0), pad=1)
+        assert got == pytest.approx(want, rel=1e-12)
+        direct = mnn.predict_ms(N, C, H, H, K, k, k, mnn.Scheme(mnn.SCHEME_DIRECT, 0, mnn.GEMM_FP32, 0, -1.0), pad=1)
+        assert direct == pytest.approx(max(2.0 * N * K * C * H * H * 9 / 1e14, (x_b + y_b + 4.0 * K * C * 9) / 4e12) * 1e3 + 0.01, rel=1e-12)
+        # a launch-bound layer: three kernels cost three schedule terms, one kernel one
+        tiny_w = mnn.predict_ms(1, 16, 8, 8, 16, 3, 3, mnn.Scheme(mnn.SCHEME_WINOGRAD, 2, 0, 0, -1.0), pad=1)
+        tiny_d = mnn.predict_ms(1, 16, 8, 8, 16, 3, 3, mnn.Scheme(mnn.SCHEME_DIRECT, 0, 0, 0, -1.0), pad=1)
+        assert tiny_w > 0.03 and 0.01 < tiny_d < 0.011
+        with pytest.raises(mnn.MnnError):
+            mnn.set_device_model(0.0, 1.0, 0.0)
+        with pytest.raises(mnn.MnnError):
+            mnn.predict_ms(1, 16, 8, 8, 16, 3, 3, mnn.Scheme(mnn.SCHEME_GEMM1X1, 0, 0, 0, -1.0))
+    finally:
+        mnn.set_device_model(**saved)
+    assert mnn.get_device_model() == saved
+    with pytest.raises(mnn.MnnError):
+        mnn.enumerate_schemes(1, 16, 8, 8, 16, 3, 3, options=mnn.Options(prune_ratio=0.5))

@@ -115,3 +115,33 @@ def test_run_on_a_side_stream_and_timed_run():
         ms = plan.run_timed(xd, wd, bd, y, iters=3)
         assert len(ms) == m.STAGE_COUNT and all(v > 0 for v in ms)
         assert oracle.error_ratio(y.cpu().numpy(), ref) < 1e-4
+
+
+def test_calibration_and_pruned_search():
+    """The device model of the analytic cost: calibrated constants are in the range of this chip, and a search
+    pruned by the prediction still lands on a scheme about as fast as the exhaustive search's."""
+    m = mnn()
+    saved = m.get_device_model()
+    try:
+        model = m.calibrate()
+        assert 6e13 < model["flops"] < 1.6e14            # fp32 matrix-core GEMM: 60 .. 157 TFLOP/s
+        assert 2e12 < model["bytes_per_s"] < 8e12
+        assert 5e-4 < model["t_schedule_ms"] < 3e-2
+        assert m.get_device_model() == model
+        for layer in (config_layers(3)[1], config_layers(5)[1].with_batch(4)):
+            m.cache_clear()
+            with m.ConvPlan.for_layer(layer) as full:
+                timed_full = [c for c in full.candidates if c.est_ms >= 0]
+                best = min(c.est_ms for c in timed_full)
+            m.cache_clear()
+            with m.ConvPlan.for_layer(layer, options=m.Options(prune_ratio=2.0)) as pruned:
+                cands = pruned.candidates
+                timed = [c for c in cands if c.est_ms >= 0]
+                chosen = pruned.scheme
+                mine = [c for c in timed if (c.kind, c.tile_n, c.variant) == (chosen.kind, chosen.tile_n, chosen.variant)]
+            assert len(cands) == len(timed_full) and 1 <= len(timed) < len(cands), (len(timed), len(cands))
+            assert mine and mine[0].est_ms <= 1.3 * best
+            print(f"[prune] {layer.name}: timed {len(timed)} of {len(cands)}, {mine[0].est_ms:.4f} ms vs best {best:.4f} ms", flush=True)
+    finally:
+        m.set_device_model(**saved)
+        m.cache_clear()
