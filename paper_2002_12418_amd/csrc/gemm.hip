@@ -478,18 +478,13 @@ const Variant kVariants[] = {
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 }  // namespace
 
-// Variant ids: 0 = choose from the shape, 1 .. kNumVariants-1 = register-staged tiles of this file,
-// kNumVariants .. = the persistent direct-to-LDS kernels.
-int gemm_f32_variant_count() { return kNumVariants + gemm_f32_async_variant_count(); }
-const char* gemm_f32_variant_name(int v)
-{
-    if (v >= 0 && v < kNumVariants) return kVariants[v].name;
-    return gemm_f32_async_variant_name(v - kNumVariants);
-}
+// Variant ids: 0 = choose from the shape, 1 .. kNumVariants-1 = the tile configurations above.
+int gemm_f32_variant_count() { return kNumVariants; }
+const char* gemm_f32_variant_name(int v) { return (v >= 0 && v < kNumVariants) ? kVariants[v].name : nullptr; }
 
 bool gemm_f32_variant_tile(int v, int* bm, int* bn, int* bk)
 {
-    if (v < 1 || v >= kNumVariants) return false;       // the persistent kernels do not split K
+    if (v < 1 || v >= kNumVariants) return false;
     *bm = kVariants[v].bm; *bn = kVariants[v].bn; *bk = kVariants[v].bk;
     return true;
 }
@@ -528,11 +523,6 @@ hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s)
         if (p.cv_C <= 0 || p.cv_H <= 0 || p.cv_W <= 0 || p.cv_kh <= 0 || p.cv_kw <= 0 || p.cv_sh <= 0 || p.cv_sw <= 0 ||
             p.cv_dh <= 0 || p.cv_dw <= 0 || p.cv_Wo <= 0 || p.L % p.cv_Wo != 0 || p.R != p.cv_C * p.cv_kh * p.cv_kw)
             return hipErrorInvalidValue;
-        if (p.variant >= kNumVariants) return hipErrorInvalidValue;   // the direct-to-LDS kernels cannot gather
-    }
-    if (p.variant >= kNumVariants) {
-        if (p.splitk > 1) return hipErrorInvalidValue;
-        return launch_gemm_f32_async(p, p.variant - kNumVariants, s);
     }
     const bool vec = aligned16(p.B) && (p.L % 4 == 0) && (p.Ncols % 4 == 0) && (p.strideB_batch % 4 == 0) &&
                      (p.strideB_img % 4 == 0) && (p.strideB_row % 4 == 0);

@@ -94,11 +94,6 @@ struct GemmProblem {
     int cv_C, cv_H, cv_W, cv_kh, cv_kw, cv_sh, cv_sw, cv_ph, cv_pw, cv_dh, cv_dw, cv_Wo;
 };
 hipError_t launch_gemm_f32(const GemmProblem& p, hipStream_t s);
-// Persistent variant with direct-to-LDS operand copies (gemm_async.hip); needs 16-byte granules on B.
-bool gemm_f32_async_usable(const GemmProblem& p);
-int gemm_f32_async_variant_count();
-const char* gemm_f32_async_variant_name(int variant);
-hipError_t launch_gemm_f32_async(const GemmProblem& p, int variant, hipStream_t s);
 int gemm_f32_variant_count();
 const char* gemm_f32_variant_name(int variant);
 // Tile shape of a variant of precision `prec` (false for variants that cannot split K) and the scratch a
