@@ -93,7 +93,8 @@ typedef struct {
                                  (plain bf16 Winograd operands miss the 2e-2 bound for most tiles)   */
     int32_t alpha_max;        /* largest n + k - 1 the planner may generate (default 8, max 10:
                                  beyond that the fp32 error of the transforms exceeds 1e-3)          */
-    float   point_scale_f;    /* f of the Winograd generator (default 0.5)                */
+    float   point_scale_f;    /* f of the Winograd generator (default 0.5, the paper's value); 0: per alpha the f with the
+                                 least fp32 error measured: 0.5 up to alpha = 8, 0.425 for alpha = 9 and 10 */
     int32_t plan_warmup;      /* untimed launches per candidate (default 2)               */
     int32_t plan_iters;       /* timed launches per candidate (default 10)                */
     int32_t use_cache;        /* 1 (default): consult / fill the process-wide choice cache */

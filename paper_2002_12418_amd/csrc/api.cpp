@@ -100,7 +100,7 @@ int validate_options(const mnn_conv_options* in, mnn_conv_options* o)
     if (o->alpha_max <= 0) o->alpha_max = 8;
     if (o->alpha_max > kMaxAlphaT)
         return fail(MNN_E_UNSUPPORTED, "alpha_max above %d: the fp32 error of larger tiles exceeds 1e-3", kMaxAlphaT);
-    if (!(o->point_scale_f > 0.f)) return fail(MNN_E_INVALID_ARG, "point_scale_f must be positive");
+    if (!(o->point_scale_f >= 0.f)) return fail(MNN_E_INVALID_ARG, "point_scale_f must be positive (or 0: chosen per alpha)");
     if (o->plan_warmup < 0 || o->plan_iters <= 0) return fail(MNN_E_INVALID_ARG, "plan_warmup >= 0 and plan_iters > 0 required");
     if (o->force_kind < MNN_SCHEME_AUTO || o->force_kind > MNN_SCHEME_GEMM1X1)
         return fail(MNN_E_INVALID_ARG, "unknown force_kind %d", o->force_kind);
@@ -658,7 +658,11 @@ struct Impl {
             if (!winograd_kernels_available(n, k))
                 return fail(MNN_E_UNSUPPORTED, "F(%d,%d) is outside the built range (n 2..8, k 2..7, alpha <= %d)", n, k, kMaxAlphaT);
             WinogradMatrices gen, unit;
-            if (!generate_winograd(n, k, (double)o.point_scale_f, &gen))
+            // f = 0: the scale with the least fp32 error for this alpha.  Up to alpha = 8 that is the paper's 0.5;
+            // for 9 and 10 points spaced 0.425 apart bring the error down 3-5x (points further out blow up G, points
+            // closer together blow up B^T).
+            const double f = o.point_scale_f > 0.f ? (double)o.point_scale_f : (n + k - 1 >= 9 ? 0.425 : 0.5);
+            if (!generate_winograd(n, k, f, &gen))
                 return fail(MNN_E_UNSUPPORTED, "generator rejected F(%d,%d)", n, k);
             unit.n = unit.k = unit.alpha = 1;
             unit.AT.assign(1, 1.f); unit.G.assign(1, 1.f); unit.BT.assign(1, 1.f);

@@ -100,3 +100,34 @@ def test_runs_are_bit_reproducible():
             y2 = plan.run(xd, wd, bd)
             torch.cuda.synchronize()
             assert torch.equal(y1, y2), s.label(3)
+
+
+def test_point_scale_per_alpha_lowers_the_error_of_the_largest_tiles():
+    """alpha = 10 (F(8,3), F(4,7)): the paper's f = 0.5 gives 1e-4 .. 4e-4, points spaced 0.425 apart (what
+    point_scale_f = 0 selects for alpha >= 9) several times less; for alpha <= 8 the two settings are the same."""
+    m = mnn()
+    for n, k, c in ((8, 3, 96), (4, 7, 64)):
+        layer = ConvLayer(f"ps_F{n}{k}", 2, c, 33, 29, 24, k, k, 1, k // 2, 1, (-1.0, 1.0), BASE_SEED + 9600 + n + k)
+        x, w, b = draw(layer)
+        ref = oracle.conv2d(x, w, b, pad=k // 2)
+        xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+        errs = {}
+        for f in (0.5, 0.0):
+            o = m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=n, force_variant=m.WINO_UNFUSED, alpha_max=10, point_scale_f=f)
+            with m.ConvPlan.for_layer(layer, options=o) as plan:
+                y = plan.run(xd, wd, bd)
+                torch.cuda.synchronize()
+            errs[f] = oracle.error_ratio(y.cpu().numpy(), ref)
+        print(f"[point scale] F({n},{k}) C={c}: f=0.5 {errs[0.5]:.2e}, per-alpha {errs[0.0]:.2e}", flush=True)
+        assert errs[0.0] <= 3e-4 and errs[0.5] <= 1e-3
+        assert errs[0.0] < 0.7 * errs[0.5]
+    layer = ConvLayer("ps_F63", 1, 32, 20, 20, 16, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 9650)
+    x, w, b = draw(layer)
+    xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+    outs = []
+    for f in (0.5, 0.0):
+        o = m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=6, force_variant=m.WINO_UNFUSED, point_scale_f=f)
+        with m.ConvPlan.for_layer(layer, options=o) as plan:
+            outs.append(plan.run(xd, wd, bd).clone())
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1])
