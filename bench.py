@@ -49,6 +49,22 @@ def stage_work(layer, scheme, info, mnn):
     return out
 
 
+def recorded_traffic(cfg, kernel_desc):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary
+    (profiles/dominant_kernel_traffic.txt; counters cannot be read from inside this process).  None unless that file
+    has a line for this workload whose kernel description is the one found dominant in this very run."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "dominant_kernel_traffic.txt")
+    try:
+        for line in open(path):
+            f = [t.strip() for t in line.split("|")]
+            if len(f) == 6 and f[0] == f"cfg{cfg}" and f[1] == kernel_desc:
+                kib = float(f[4].split()[1]) + float(f[5].split()[1])
+                return round(kib * 1024.0)
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
 def cpu_baseline(layers):
     """The float64 oracle, as it stands, timed on the host cores over a bounded sample of the same workload:
     whole images of every layer (images are independent), as many as fit about 1.5 s of wall time per layer,
@@ -320,6 +336,7 @@ def main():
         ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roofline = {"kernel": f"{dom['layer']}: {dom['stage']} of {dom['desc']}", "bound": "hbm", "achieved": round(ach, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+    roofline["traffic"] = recorded_traffic(args.config, roofline["kernel"])
     roofline["avg_launch_ms"] = round(dom["ms"], 5)
     roofline["algorithmic_flops_per_launch"] = dom["flops"]
     roofline["algorithmic_bytes_per_launch"] = dom["bytes"]
