@@ -292,13 +292,15 @@ hipError_t launch_fused_t(const WinoGeom& g, const float* AT, const float* Ub, c
 constexpr int bkg_for(int alpha) { return alpha <= 6 ? 4 : 2; }
 
 constexpr bool fits_big(int n, int k) { return (2 * (4 * (n + k - 1) + 4 * n * n)) <= 190; }
+// one 16x16 tile per wavefront must leave room for two wavefronts per SIMD (256 registers each)
+constexpr bool fits_small(int n, int k) { return 4 * (n + k - 1) + 4 * n * n <= 230; }
 
 }  // namespace
 
 bool wino_fused_available(int n, int k)
 {
     const int a = n + k - 1;
-    return n >= 2 && k >= 2 && a <= 8 && winograd_kernels_available(n, k);
+    return n >= 2 && k >= 2 && a <= kMaxAlphaT && fits_small(n, k) && winograd_kernels_available(n, k);
 }
 
 bool wino_fused_has_big_block(int n, int k) { return wino_fused_available(n, k) && fits_big(n, k); }
@@ -325,6 +327,8 @@ hipError_t launch_wino_fused(const WinoGeom& g, int config, const float* AT, con
     MNN_FUSED(2, 5) MNN_FUSED(3, 5) MNN_FUSED(4, 5)
     MNN_FUSED(2, 6) MNN_FUSED(3, 6)
     MNN_FUSED(2, 7)
+    // alpha = 9 and 10 where the n x n outputs still fit the registers
+    MNN_FUSED(6, 4) MNN_FUSED(5, 5) MNN_FUSED(6, 5) MNN_FUSED(4, 6) MNN_FUSED(5, 6) MNN_FUSED(3, 7) MNN_FUSED(4, 7)
 #undef MNN_FUSED
     return hipErrorInvalidValue;
 }
