@@ -375,7 +375,9 @@ void mnn_conv_cache_clear(void);
 int mnn_conv_cache_save(const char* path);
 int mnn_conv_cache_load(const char* path);
 
+/* Message of the last failure on the calling thread (empty string if none).  Host. */
 const char* mnn_last_error(void);
+/* 100 * major + minor of this ABI; plan-cache files carry their own format number. */
 int mnn_version(void);
 
 #ifdef __cplusplus

@@ -784,7 +784,7 @@ int mnn_conv_cache_load(const char* path)
 
 const char* mnn_last_error(void) { return g_err.c_str(); }
 
-int mnn_version(void) { return 100; }
+int mnn_version(void) { return 110; }
 
 }  // extern "C"
 
