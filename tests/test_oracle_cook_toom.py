@@ -1,6 +1,8 @@
 """Pins for the exact-rational transform generator (oracle/cook_toom.py)."""
 from fractions import Fraction as Fr
 
+import os
+
 import numpy as np
 import pytest
 
@@ -38,6 +40,23 @@ def test_identity_on_random_rationals_is_correlation_not_convolution():
     assert y != flipped
 
 
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def read_matrices(name):
+    """AT, G, BT as lists of rows of Fractions from a tests/golden/*.txt fixture."""
+    mats, cur = {}, None
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line in ("AT", "G", "BT"):
+            cur = mats.setdefault(line, [])
+        else:
+            cur.append([Fr(t) for t in line.split()])
+    return mats["AT"], mats["G"], mats["BT"]
+
+
 def test_point_sequence():
     assert cook_toom.points(4) == [0, Fr(1, 2), Fr(-1, 2)]
     assert cook_toom.points(6) == [0, Fr(1, 2), Fr(-1, 2), 1, -1]
@@ -53,10 +72,10 @@ def test_f23_worked_values_half_points():
     """F(2,3), points (0, 1/2, -1/2, inf), worked by hand from the interpolation formula:
     M_0 = x^2 - 1/4, N_0 = -1/4; M_1 = x^2 + x/2, N_1 = 1/2; M_2 = x^2 - x/2, N_2 = 1/2; M = x^3 - x/4."""
     AT, G, BT = cook_toom.matrices(2, 3, Fr(1, 2))
+    AT_w, G_w, BT_w = read_matrices("winograd_F23_half_points.txt")
+    assert AT == AT_w and G == G_w and BT == BT_w
     h, q = Fr(1, 2), Fr(1, 4)
-    assert AT == [[1, 1, 1, 0], [0, h, -h, 1]]
-    assert G == [[-4, 0, 0], [2, 1, h], [2, -1, h], [0, 0, 1]]
-    assert BT == [[-q, 0, 1, 0], [0, h, 1, 0], [0, -h, 1, 0], [0, -q, 0, 1]]
+    assert AT == [[1, 1, 1, 0], [0, h, -h, 1]] and BT[0] == [-q, 0, 1, 0]      # the fixture is what the docstring says
 
 
 def _rank_one_terms(AT, G, BT):
@@ -68,20 +87,14 @@ def _rank_one_terms(AT, G, BT):
 def test_f23_unit_points_equal_the_classic_matrices_up_to_scaling():
     # The widely published F(2,3) matrices for points (0, 1, -1, inf) (Lavin & Gray, "Fast algorithms
     # for convolutional neural networks", the work the paper cites for Winograd convolution).
-    BT_c = [[1, 0, -1, 0], [0, 1, 1, 0], [0, -1, 1, 0], [0, 1, 0, -1]]
-    G_c = [[1, 0, 0], [0.5, 0.5, 0.5], [0.5, -0.5, 0.5], [0, 0, 1]]
-    AT_c = [[1, 1, 1, 0], [0, 1, -1, -1]]
+    AT_c, G_c, BT_c = read_matrices("winograd_F23_unit_points.txt")
     AT, G, BT = cook_toom.matrices(2, 3, Fr(1))
     np.testing.assert_allclose(_rank_one_terms(AT, G, BT), _rank_one_terms(AT_c, G_c, BT_c), atol=0)
 
 
 def test_f43_unit_points_equal_the_classic_matrices_up_to_scaling():
     # F(4,3) for points (0, 1, -1, 2, -2, inf) from the same publication.
-    BT_c = [[4, 0, -5, 0, 1, 0], [0, -4, -4, 1, 1, 0], [0, 4, -4, -1, 1, 0],
-            [0, -2, -1, 2, 1, 0], [0, 2, -1, -2, 1, 0], [0, 4, 0, -5, 0, 1]]
-    G_c = [[1 / 4, 0, 0], [-1 / 6, -1 / 6, -1 / 6], [-1 / 6, 1 / 6, -1 / 6],
-           [1 / 24, 1 / 12, 1 / 6], [1 / 24, -1 / 12, 1 / 6], [0, 0, 1]]
-    AT_c = [[1, 1, 1, 1, 1, 0], [0, 1, -1, 2, -2, 0], [0, 1, 1, 4, 4, 0], [0, 1, -1, 8, -8, 1]]
+    AT_c, G_c, BT_c = read_matrices("winograd_F43_unit_points.txt")
     AT, G, BT = cook_toom.matrices(4, 3, Fr(1))
     np.testing.assert_allclose(_rank_one_terms(AT, G, BT), _rank_one_terms(AT_c, G_c, BT_c), atol=1e-15)
 

@@ -41,3 +41,20 @@ def test_strassen_rule():
     assert cm.strassen_should_recurse(32, 32, 32)
     assert not cm.strassen_should_recurse(30, 30, 30)
     assert not cm.strassen_should_recurse(2, 2, 2)
+
+
+def test_strassen_rule_on_the_papers_table():
+    """The matrix sizes of the paper's Strassen table (tests/golden/strassen_table3.txt): the two sides of the rule as
+    worked by hand in the fixture, and the rule's verdict -- the paper applied Strassen to all four."""
+    import os
+    from fractions import Fraction
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "strassen_table3.txt")
+    rows = [[int(t) for t in line.split()] for line in open(path) if line.strip() and not line.startswith("#")]
+    assert [r[:3] for r in rows] == [[256, 256, 256], [512, 512, 512], [512, 512, 1024], [1024, 1024, 1024]]
+    h = Fraction(1, 2)
+    for a, b, c, ms_without, ms_with, saved, extra in rows:
+        n, k, m = a, b, c
+        assert m * n * k - 7 * (m * h) * (n * h) * (k * h) == saved
+        assert 4 * (m * h) * (k * h) + 4 * (n * h) * (k * h) + 7 * (m * h) * (n * h) == extra
+        assert cm.strassen_should_recurse(n, k, m) == (saved > extra) is True
+        assert ms_with <= ms_without
