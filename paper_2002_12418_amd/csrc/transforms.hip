@@ -168,7 +168,9 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg
 }
 
 // ---------------------------------------------------------------- output: y = A^T m A + bias
-template <int NT, int A>
+// STREAM: M is larger than the last-level cache, so this (its last) read goes past the caches instead of
+// evicting what the next kernel could still use; small M is read normally (it is still resident from the GEMM).
+template <int NT, int A, bool STREAM>
 __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatArg<NT, A> at,
                                                                const float* __restrict__ M,
                                                                const float* __restrict__ bias,
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatAr
     for (int a = 0; a < A; ++a) {
         float mrow[A];
 #pragma unroll
-        for (int b = 0; b < A; ++b) mrow[b] = mp[(long long)(a * A + b) * plane];
+        for (int b = 0; b < A; ++b) mrow[b] = STREAM ? __builtin_nontemporal_load(mp + (long long)(a * A + b) * plane) : mp[(long long)(a * A + b) * plane];
 #pragma unroll
         for (int i = 0; i < NT; ++i)
 #pragma unroll
@@ -247,6 +249,9 @@ hipError_t launch_input_t(const WinoGeom& g, const float* BT, const float* x, fl
     MatArg<A, A> m;
     for (int i = 0; i < A; ++i)
         for (int j = 0; j < A; ++j) m.v[i][j] = BT[i * A + j];
+    // V is stored normally even when it is far larger than the caches: stores that go past them make this
+    // kernel 25-35 % faster run alone but slower in sequence -- normal stores park about half of V in the 256 MB
+    // last-level cache, its write-back overlaps the matrix-core-bound GEMM, and the GEMM finds that half there.
     if (g.blocked) {
         const long long total = (long long)g.cchunks * ((g.P + 15) / 16) * 64;
         const unsigned blocks = (unsigned)((total + 255) / 256);
@@ -271,7 +276,12 @@ hipError_t launch_output_t(const WinoGeom& g, const float* AT, const float* M, c
     // 8-byte stores need every tile row start 8-byte aligned: even n, even W_o, aligned base
     int vec2 = (NT % 2 == 0) && (g.Wo % 2 == 0) && ((reinterpret_cast<uintptr_t>(y) & 7u) == 0);
     if (NT == 4 && (g.Wo % 4 == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0)) vec2 = 2;   // whole-tile float4 rows
-    hipLaunchKernelGGL((output_transform_kernel<NT, A>), dim3(blocks), dim3(256), 0, s, g, m, M, bias, y, vec2);
+    // 256 MB of last-level cache on this part; well above half of it nothing of M survives until it is read
+    const bool stream = (double)A * A * g.K * g.ldp * sizeof(float) > 160e6;
+    if (stream)
+        hipLaunchKernelGGL((output_transform_kernel<NT, A, true>), dim3(blocks), dim3(256), 0, s, g, m, M, bias, y, vec2);
+    else
+        hipLaunchKernelGGL((output_transform_kernel<NT, A, false>), dim3(blocks), dim3(256), 0, s, g, m, M, bias, y, vec2);
     return hipGetLastError();
 }
 
