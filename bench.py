@@ -52,12 +52,15 @@ def stage_work(layer, scheme, info, mnn):
 def recorded_traffic(cfg, kernel_desc):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary
     (profiles/dominant_kernel_traffic.txt; counters cannot be read from inside this process).  None unless that file
-    has a line for this workload whose kernel description is the one found dominant in this very run."""
+    has a line for this workload whose layer and scheme are those of the kernel found dominant in this very run."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "dominant_kernel_traffic.txt")
+
+    def scheme_of(desc):        # layer and scheme; the GEMM tile configuration is re-tuned per process and moves the same bytes
+        return desc.split(" gemm=")[0]
     try:
         for line in open(path):
             f = [t.strip() for t in line.split("|")]
-            if len(f) == 6 and f[0] == f"cfg{cfg}" and f[1] == kernel_desc:
+            if len(f) == 6 and f[0] == f"cfg{cfg}" and scheme_of(f[1]) == scheme_of(kernel_desc):
                 kib = float(f[4].split()[1]) + float(f[5].split()[1])
                 return round(kib * 1024.0)
     except (OSError, ValueError, IndexError):
