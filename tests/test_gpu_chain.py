@@ -166,3 +166,37 @@ def test_chain_call_order_errors():
     with pytest.raises(ValueError):
         ch.set_weights(0, torch.zeros(3, 3, device="cuda"))
     ch.close()
+
+
+def test_chain_on_a_side_stream_and_with_bf16_operands():
+    """The chain enqueues on the stream it is given (eager and graph replay), and carries the planner's options:
+    with allow_bf16 the layers may take split-bf16 operands and the result stays within the bf16 bound."""
+    m = mnn()
+    layers = chain_layers("resnet18_trunk", 2)
+    x0, wb = draw_chain(layers)
+    ref = oracle_chain(layers, x0, wb)
+    side = torch.cuda.Stream()
+    for options, tol in ((None, None), (m.Options(allow_bf16=1), 2e-2)):
+        m.cache_clear()
+        ch = m.ConvChain(layers, options=options, stream=side)
+        keep = []
+        for i, (w, b) in enumerate(wb):
+            wd, bd = torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda()
+            keep.append((wd, bd))
+        torch.cuda.synchronize()
+        for i, (wd, bd) in enumerate(keep):
+            ch.set_weights(i, wd, bd, stream=side)
+        xd = torch.from_numpy(x0).cuda()
+        torch.cuda.synchronize()
+        y = torch.empty(layers[-1].out_shape, device="cuda")
+        ch.run(xd, y, stream=side)
+        side.synchronize()
+        y_eager = y.clone()
+        err = oracle.error_ratio(y_eager.cpu().numpy(), ref[-1])
+        assert err <= (tol if tol is not None else bound(m, ch, len(layers))), err
+        yg = ch.capture(xd)
+        ch.replay(stream=side)
+        side.synchronize()
+        assert torch.equal(yg, y_eager)
+        ch.close()
+    m.cache_clear()
