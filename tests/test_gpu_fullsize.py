@@ -106,3 +106,22 @@ def test_operands_of_two_gib_take_the_wide_loader():
         assert err <= 1e-4
         assert bool(torch.isfinite(y).all())
         del y
+
+
+def test_rect_layers_full_tensor():
+    """The factorised 7-tap layers bench.py reports (rectangular_kernels), planner's choice, whole output."""
+    from conv_workloads import rect_layers
+    m = mnn()
+    for layer in rect_layers(16):
+        x, w, b = draw(layer)
+        ref = oracle.conv2d(x, w, b, stride=layer.stride, pad=layer.pad, dil=layer.dil)
+        xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+        for opt in (None, m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=2)):
+            with m.ConvPlan.for_layer(layer, options=opt) as plan:
+                y = torch.full(plan.out_shape, float("nan"), device="cuda")
+                plan.run(xd, wd, bd, y)
+                torch.cuda.synchronize()
+                s, desc = plan.scheme, plan.describe()
+            err = oracle.error_ratio(y.cpu().numpy(), ref)
+            print(f"[rect] {layer.name} {desc} err={err:.2e}", flush=True)
+            assert err <= tol_for(s, layer.k_long, m)

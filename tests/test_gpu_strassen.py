@@ -97,3 +97,20 @@ def test_planner_times_strassen_like_any_other_candidate():
         torch.cuda.synchronize()
     assert oracle.error_ratio(y.cpu().numpy(), oracle.conv2d(x, w, b)) <= 1e-4 * (1 + 4 * chosen.variant)
     m.cache_clear()
+
+
+@pytest.mark.parametrize("levels", [1, 2])
+def test_strassen_at_the_size_of_the_last_pointwise_layer(levels):
+    """1024 x 1024 x 784 (cfg4's last layer as one product), the size bench.py times."""
+    m = mnn()
+    M, R, N = 1024, 1024, 784
+    rng = np.random.Generator(np.random.PCG64(BASE_SEED + 4040 + levels))
+    At = rng.normal(0, np.sqrt(2.0 / R), (R, M)).astype(np.float32)
+    B = rng.uniform(0, 1, (R, N)).astype(np.float32)
+    ref = At.astype(np.float64).T @ B.astype(np.float64)
+    D = torch.full((M, N), float("nan"), device="cuda")
+    with m.StrassenGemm(M, N, R, levels) as sg:
+        sg.set_left(torch.from_numpy(At).cuda())
+        sg.run(torch.from_numpy(B).cuda(), D)
+        torch.cuda.synchronize()
+    assert oracle.error_ratio(D.cpu().numpy(), ref) <= 1e-4 * (1 + 4 * levels)
