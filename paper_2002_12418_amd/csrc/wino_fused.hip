@@ -290,6 +290,10 @@ hipError_t launch_fused_t(const WinoGeom& g, const float* AT, const float* Ub, c
 // registers per lane: 4*alpha accumulators + 4*n^2 outputs per 16x16 tile
 // 4-channel groups per chunk: three stages must fit the LDS budget of the configuration
 constexpr int bkg_for(int alpha) { return alpha <= 6 ? 4 : 2; }
+// Stages of the operand ring.  Two: one chunk being multiplied, one in flight.  A third stage (or a fourth) buys
+// less than the workgroups per CU it costs: at 16 KiB per stage, two stages let five 32 x 32 workgroups share a CU
+// instead of three (F(2,7) C = 64: 0.346 -> 0.320 ms, F(4,5) C = 128: 0.111 -> 0.103 ms).
+constexpr int kStages = 2;
 
 constexpr bool fits_big(int n, int k) { return (2 * (4 * (n + k - 1) + 4 * n * n)) <= 190; }
 // one 16x16 tile per wavefront must leave room for two wavefronts per SIMD (256 registers each)
@@ -317,9 +321,9 @@ hipError_t launch_wino_fused(const WinoGeom& g, int config, const float* AT, con
 #define MNN_FUSED(NN, KK)                                                                       \
     if (g.n == NN && g.k == KK) {                                                                \
         if constexpr (fits_big(NN, KK)) {                                                        \
-            if (config == 1) return launch_fused_t<NN, KK, 2, 1, 2, 4, bkg_for(NN + KK - 1), 3>(g, AT, Ub, Vb, bias, y, s);  \
+            if (config == 1) return launch_fused_t<NN, KK, 2, 1, 2, 4, bkg_for(NN + KK - 1), kStages>(g, AT, Ub, Vb, bias, y, s);  \
         }                                                                                        \
-        return launch_fused_t<NN, KK, 1, 1, 2, 2, bkg_for(NN + KK - 1), 3>(g, AT, Ub, Vb, bias, y, s);                       \
+        return launch_fused_t<NN, KK, 1, 1, 2, 2, bkg_for(NN + KK - 1), kStages>(g, AT, Ub, Vb, bias, y, s);                       \
     }
     MNN_FUSED(2, 2) MNN_FUSED(3, 2) MNN_FUSED(4, 2) MNN_FUSED(5, 2) MNN_FUSED(6, 2) MNN_FUSED(7, 2)
     MNN_FUSED(2, 3) MNN_FUSED(3, 3) MNN_FUSED(4, 3) MNN_FUSED(5, 3) MNN_FUSED(6, 3)
