@@ -343,12 +343,20 @@ def main():
     roofline["avg_launch_ms"] = round(dom["ms"], 5)
     roofline["algorithmic_flops_per_launch"] = dom["flops"]
     roofline["algorithmic_bytes_per_launch"] = dom["bytes"]
+    # the same fractions against what this GPU reaches in two probes (matrix-core issue loop, plain copy kernel);
+    # measured after the timed region so that they cannot disturb it
+    peaks = mnn.measure_device_peaks(stream)
+    measured = {"mfma_f32_TFLOP/s": round(peaks["mfma_f32_flops"] / 1e12, 1), "copy_GB/s": round(peaks["copy_bytes_per_s"] / 1e9, 1)}
+    measured["frac"] = round(ach / (measured["mfma_f32_TFLOP/s"] if dom["stage"] == "gemm" else measured["copy_GB/s"]), 4)
+    roofline["measured_peak"] = measured
     roofline["stages"] = {
         s: {"ms_per_step": round(v["ms"], 5), "launches_per_step": v["launches"],
             "TFLOP/s": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2),
             "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1),
             "frac_mfma": round(v["flops"] / (v["ms"] * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
-            "frac_hbm": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+            "frac_hbm": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "frac_measured_mfma": round(v["flops"] / (v["ms"] * 1e-3) / peaks["mfma_f32_flops"], 4),
+            "frac_measured_copy": round(v["bytes"] / (v["ms"] * 1e-3) / peaks["copy_bytes_per_s"], 4)}
         for s, v in main_res["stage_tot"].items() if v["launches"] and v["ms"] > 0}
 
     out = {

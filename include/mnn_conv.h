@@ -248,6 +248,20 @@ int mnn_conv_calibrate(void* stream, mnn_device_model* out);
 int mnn_conv_predict_ms(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_scheme* scheme,
                         double* ms);
 
+/*
+ * Upper limits of the two device rates of Section 3.2 (2), measured on `stream` (about 20 ms): the rate at
+ * which the GPU issues fp32 matrix-core instructions from registers with no memory access in the loop, and the
+ * rate of a plain 16-byte copy kernel over 256 MiB (bytes read plus bytes written per second).  These are the
+ * ceilings a roofline fraction can be taken against next to the published figures; the cost model does not
+ * use them.  Allocates and frees its own device buffers; synchronises `stream`.  `out` is host memory.
+ * Errors: MNN_E_INVALID_ARG (NULL out), MNN_E_NO_DEVICE, MNN_E_OOM, MNN_E_HIP.
+ */
+typedef struct {
+    double mfma_f32_flops;    /* FLOP/s of back-to-back fp32 32x32x2 matrix-core instructions, whole device */
+    double copy_bytes_per_s;  /* B/s (read + write) of a streaming copy kernel                              */
+} mnn_device_peaks;
+int mnn_measure_device_peaks(void* stream, mnn_device_peaks* out);
+
 /* The candidate list mnn_conv_plan would time for this layer, without touching
  * the device.  Host only.  Same cap / count convention as above. */
 int mnn_conv_enumerate(const mnn_conv_shape* shape, const mnn_conv_geom* geom,

@@ -49,6 +49,10 @@ class _Options(ctypes.Structure):
                 ("plan_warmup", c_int32), ("plan_iters", c_int32), ("use_cache", c_int32), ("prune_ratio", c_float)]
 
 
+class _DevicePeaks(ctypes.Structure):
+    _fields_ = [("mfma_f32_flops", c_double), ("copy_bytes_per_s", c_double)]
+
+
 class _DeviceModel(ctypes.Structure):
     _fields_ = [("flops", c_double), ("bytes_per_s", c_double), ("t_schedule_ms", c_double)]
 
@@ -133,6 +137,7 @@ def _load() -> ctypes.CDLL:
     L.mnn_conv_get_device_model.argtypes = [POINTER(_DeviceModel)]
     L.mnn_conv_set_device_model.argtypes = [POINTER(_DeviceModel)]
     L.mnn_conv_calibrate.argtypes = [vp, POINTER(_DeviceModel)]
+    L.mnn_measure_device_peaks.argtypes = [vp, POINTER(_DevicePeaks)]
     L.mnn_conv_predict_ms.argtypes = [POINTER(_Shape), POINTER(_Geom), POINTER(_Scheme), POINTER(c_double)]
     L.mnn_conv_cache_size.argtypes = []
     L.mnn_conv_cache_clear.argtypes = []
@@ -342,6 +347,12 @@ def calibrate(stream=None) -> dict:
     m = _DeviceModel()
     _check(lib.mnn_conv_calibrate(_stream_handle(stream), byref(m)))
     return {"flops": m.flops, "bytes_per_s": m.bytes_per_s, "t_schedule_ms": m.t_schedule_ms}
+
+
+def measure_device_peaks(stream=None) -> dict:
+    m = _DevicePeaks()
+    _check(lib.mnn_measure_device_peaks(_stream_handle(stream), byref(m)))
+    return {"mfma_f32_flops": m.mfma_f32_flops, "copy_bytes_per_s": m.copy_bytes_per_s}
 
 
 def predict_ms(n, c_in, h, w, c_out, kh, kw, scheme: "Scheme", stride=1, pad=0, dil=1) -> float:

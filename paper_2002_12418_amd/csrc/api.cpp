@@ -672,6 +672,65 @@ int mnn_conv_calibrate(void* stream, mnn_device_model* out)
     return MNN_OK;
 }
 
+int mnn_measure_device_peaks(void* stream, mnn_device_peaks* out)
+{
+    if (!out) return fail(MNN_E_INVALID_ARG, "out is NULL");
+    int ndev = 0;
+    hipError_t e = hipGetDeviceCount(&ndev);
+    if (e != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        return fail(MNN_E_NO_DEVICE, "no HIP device available");
+    }
+    hipStream_t s = (hipStream_t)stream;
+    hipDeviceProp_t prop{};
+    int dev = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess || (e = hipGetDeviceProperties(&prop, dev)) != hipSuccess)
+        return fail_hip(e, "device properties");
+    const int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    const int wgs = cus * 8, iters = 2048;                               // 8 waves per SIMD, 4*iters instructions per wave
+    const size_t copy_bytes = (size_t)256 << 20;
+    float *b = nullptr, *d = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = MNN_OK;
+    mnn_device_peaks m{};
+    do {
+        if ((e = hipMalloc((void**)&b, copy_bytes)) != hipSuccess || (e = hipMalloc((void**)&d, copy_bytes)) != hipSuccess) {
+            (void)hipGetLastError();
+            rc = fail(MNN_E_OOM, "device peaks: %s", hipGetErrorString(e));
+            break;
+        }
+        if ((e = hipMemsetAsync(b, 0, copy_bytes, s)) != hipSuccess || (e = hipEventCreate(&e0)) != hipSuccess ||
+            (e = hipEventCreate(&e1)) != hipSuccess) {
+            rc = fail_hip(e, "device peaks set-up");
+            break;
+        }
+        auto timed = [&](int reps, const std::function<hipError_t()>& launch, double* ms_each) -> int {
+            hipError_t er = launch();                                    // warm-up
+            if (er == hipSuccess) er = hipEventRecord(e0, s);
+            for (int i = 0; i < reps && er == hipSuccess; ++i) er = launch();
+            if (er == hipSuccess) er = hipEventRecord(e1, s);
+            if (er == hipSuccess) er = hipEventSynchronize(e1);
+            float ms = 0.f;
+            if (er == hipSuccess) er = hipEventElapsedTime(&ms, e0, e1);
+            if (er != hipSuccess) return fail_hip(er, "device peaks run");
+            *ms_each = (double)ms / reps;
+            return MNN_OK;
+        };
+        double ms = 0.0;
+        if ((rc = timed(3, [&] { return launch_mfma_issue(d, wgs, iters, s); }, &ms))) break;
+        m.mfma_f32_flops = (double)wgs * 4 * (4.0 * iters) * (2.0 * 32 * 32 * 2) / (ms * 1e-3);
+        if ((rc = timed(10, [&] { return launch_stream_copy(b, d, copy_bytes / 4, cus * 16, s); }, &ms))) break;
+        m.copy_bytes_per_s = 2.0 * (double)copy_bytes / (ms * 1e-3);
+    } while (false);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (b) (void)hipFree(b);
+    if (d) (void)hipFree(d);
+    if (rc) return rc;
+    *out = m;
+    return MNN_OK;
+}
+
 int mnn_conv_predict_ms(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_scheme* scheme, double* ms)
 {
     if (!scheme || !ms) return fail(MNN_E_INVALID_ARG, "NULL argument");

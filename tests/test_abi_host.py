@@ -167,6 +167,10 @@ def test_plan_argument_validation(mnn):
             mnn.ConvPlan(1, 4, 8, 8, 4, 3, 3, pad=1)
         assert e.value.code == -5                                     # MNN_E_NO_DEVICE, never a CPU fallback
         assert "device" in str(e.value).lower()
+        with pytest.raises(mnn.MnnError) as e:
+            mnn.measure_device_peaks()
+        assert e.value.code == -5
+    assert mnn.lib.mnn_measure_device_peaks(None, None) == -1          # NULL out
 
 
 def test_gemm_variant_table(mnn):

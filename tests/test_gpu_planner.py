@@ -117,6 +117,16 @@ def test_run_on_a_side_stream_and_timed_run():
         assert oracle.error_ratio(y.cpu().numpy(), ref) < 1e-4
 
 
+def test_measured_device_peaks():
+    """The two probes behind the measured roofline ceilings: the matrix-core issue rate cannot exceed the published
+    fp32 figure (256 CUs x 256 FLOP/clk x 2.4 GHz) and a copy kernel cannot exceed the published HBM rate; both must
+    be above what the library's own kernels reach."""
+    m = mnn()
+    p = m.measure_device_peaks()
+    assert 1.0e14 < p["mfma_f32_flops"] <= 1.02 * 157.3e12, p
+    assert 3.0e12 < p["copy_bytes_per_s"] <= 8.0e12, p
+
+
 def test_calibration_and_pruned_search():
     """The device model of the analytic cost: calibrated constants are in the range of this chip, and a search
     pruned by the prediction still lands on a scheme about as fast as the exhaustive search's."""
