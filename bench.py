@@ -198,6 +198,27 @@ def run_rect(batch, stream, mnn, torch):
     return res
 
 
+def run_selection_table(stream, mnn):
+    """The scheme-selection comparison of Section 3.2 (Table 1) on this device: for the paper's three settings the
+    measured time of the sliding window, of the smallest and the largest Winograd tile the search admits, and of the
+    planner's choice (all from the planner's own timing of its candidates; best kernel arrangement of each)."""
+    from conv_workloads import selection_table_layers
+    res = []
+    for batch in (1, 16):
+        for layer in selection_table_layers(batch):
+            with mnn.ConvPlan.for_layer(layer, stream=stream) as plan:
+                timed = [c for c in plan.candidates if c.est_ms >= 0]
+                wino = [c for c in timed if c.kind == mnn.SCHEME_WINOGRAD]
+                n_min, n_max = min(c.tile_n for c in wino), max(c.tile_n for c in wino)
+                best = lambda cs: round(min(c.est_ms for c in cs), 4)
+                res.append({"layer": layer.name, "batch": batch,
+                            "sliding_ms": best([c for c in timed if c.kind == mnn.SCHEME_DIRECT]),
+                            "wino_min": {"n": n_min, "ms": best([c for c in wino if c.tile_n == n_min])},
+                            "wino_max": {"n": n_max, "ms": best([c for c in wino if c.tile_n == n_max])},
+                            "planner": {"kernels": plan.describe(), "ms": round(plan.scheme.est_ms, 4)}})
+    return res
+
+
 def run_strassen(mnn, torch):
     """Section 3.3.2 / Table 3 on this device: the plain fp32 product against 1 and 2 levels of Strassen, on the
     paper's sizes and on sizes where the matrix cores, not launch latency, set the time.  (a, b, c) = [a,b] x [b,c]."""
@@ -408,6 +429,7 @@ def main():
                                             for i, e in enumerate(compared)}}
         # preparation-execution decoupling over a chain of layers (the launch-bound batch-1 regime and batch 32)
         # kernels with a single row or column (factorised 7-tap layers): planner's choice next to the sliding window
+        out["selection_table"] = run_selection_table(stream, mnn)
         out["rectangular_kernels"] = run_rect(16, stream, mnn, torch)
         out["strassen"] = run_strassen(mnn, torch)
         out["chained_execution"] = [run_chain("resnet18_trunk", b, 200 if b == 1 else 50, 10, stream, mnn, torch)

@@ -195,3 +195,16 @@ def rect_layers(n: int = 16) -> List[ConvLayer]:
         L(2, "incep192_17x17_1x7", 192, 192, 1, 7, (0, 3)),
         L(3, "incep192_17x17_7x1", 192, 192, 7, 1, (3, 0)),
     ]
+
+
+def selection_table_layers(n: int = 1) -> List[ConvLayer]:
+    """The three convolution settings (k, i_c, o_c, size) of the paper's scheme-selection comparison (Table 1):
+    (2, 3, 16, 224), (2, 512, 512, 16), (3, 64, 64, 112).  The paper states neither padding nor batch: no padding
+    for the 2-tap kernels, 'same' padding for the 3-tap one, batch `n`."""
+    def L(i, name, c, k, hw, kk, pad):
+        return ConvLayer(name, n, c, hw, hw, k, kk, kk, 1, pad, 1, (-1.0, 1.0), BASE_SEED + 9800 + i)
+    return [
+        L(0, "sel3to16_224x224_k2", 3, 16, 224, 2, 0),
+        L(1, "sel512_16x16_k2", 512, 512, 16, 2, 0),
+        L(2, "sel64_112x112_k3", 64, 64, 112, 3, 1),
+    ]

@@ -288,7 +288,8 @@ hipError_t launch_fused_t(const WinoGeom& g, const float* AT, const float* Ub, c
 }
 
 // registers per lane: 4*alpha accumulators + 4*n^2 outputs per 16x16 tile
-// 4-channel groups per chunk: three stages must fit the LDS budget of the configuration
+// 4-channel groups per chunk: a stage of both operands is BKG * alpha * (MG + PG) blocks of 256 bytes,
+// 16 to 24 KiB for 32 x 32 blocks and twice that for 64 x 64
 constexpr int bkg_for(int alpha) { return alpha <= 6 ? 4 : 2; }
 // Stages of the operand ring.  Two: one chunk being multiplied, one in flight.  A third stage (or a fourth) buys
 // less than the workgroups per CU it costs: at 16 KiB per stage, two stages let five 32 x 32 workgroups share a CU

@@ -8,7 +8,7 @@ import pytest
 import torch
 
 import oracle
-from conv_workloads import config_layers, draw, small_parity_layers
+from conv_workloads import config_layers, draw, selection_table_layers, small_parity_layers
 
 pytestmark = pytest.mark.gpu
 
@@ -85,6 +85,16 @@ def test_planner_choice_is_correct_and_listed(layer):
     assert err <= tol_for(scheme, layer.k_long)
     if layer.stride != 1:
         assert scheme.kind == m.SCHEME_DIRECT
+
+
+@pytest.mark.parametrize("layer", selection_table_layers(1), ids=lambda l: l.name)
+def test_selection_table_settings_every_scheme(layer):
+    """The three settings of the paper's scheme-selection comparison (Table 1): 2-tap kernels with 3 and 512
+    channels, a 3-tap kernel with 64: every forced scheme and the planner's pick against the oracle."""
+    for label, opt in forced_options(layer) + [("planner", None)]:
+        print(f"[case] {layer.name} {label}", flush=True)
+        err, scheme = run_and_compare(layer, opt)
+        assert err <= tol_for(scheme, layer.k_long), (layer.name, label, err)
 
 
 BF16_TOL = 2e-2        # bound for the bf16-matrix-core variants
