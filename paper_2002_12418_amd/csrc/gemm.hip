@@ -51,12 +51,19 @@ __device__ __forceinline__ int xcd_remap(int bid, int total)
 // the compiler can count exactly how many loads are in flight (a branch around a load forces it to wait
 // for all of them).  Needs every operand of one batch to span less than 2 GiB; larger ones take the
 // pointer-based loader (BUF = false).
-template <int BM, int BN, int BK, int WM, int WN, int MODE, int PF = 1, bool BUF = true>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, int tilesM, int tilesN, int total,
+//
+// WK: wavefronts along the reduction.  The WM x WN grid of wavefronts is repeated WK times; copy wk multiplies
+// rows [wk * BK/WK, (wk+1) * BK/WK) of every chunk, and the WK partial blocks are added through LDS (in wk
+// order) before the store.  A 32 x 32 output tile is one MFMA tile: with WK = 4 its reduction still runs on all
+// four SIMDs of a CU, so that a problem with few output elements and a long reduction (batch-1 layers) spreads
+// over four times as many workgroups without a second kernel.
+template <int BM, int BN, int BK, int WM, int WN, int MODE, int PF = 1, bool BUF = true, int WK = 1>
+__global__ __launch_bounds__(WM * WN * WK * 64) void gemm_f32_kernel(GemmProblem p, int tilesM, int tilesN, int total,
                                                                 unsigned a_bytes, unsigned b_bytes, int vecD, int ldc)
 {
     static_assert(PF == 1 || PF % 2 == 0, "the LDS buffer index is derived from the stage index");
-    constexpr int NT = WM * WN * 64;
+    constexpr int NT = WM * WN * WK * 64;
+    constexpr int KW = BK / WK;               // reduction rows of a chunk per wavefront
     constexpr int TM = BM / WM / 32;          // 32x32 tiles per wavefront along m
     constexpr int TN = BN / WN / 32;          // ... along columns
     constexpr int A4 = BK * BM / 4;           // float4 slots of the A tile
@@ -64,20 +71,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
     constexpr int LA = A4 / NT;               // slots per thread
     constexpr int LB = B4 / NT;
     static_assert(A4 % NT == 0 && B4 % NT == 0, "tile must divide evenly over the workgroup");
-    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % 2 == 0, "tile shape");
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BK % (2 * WK) == 0, "tile shape");
 
     // one LDS block: the operand double buffer during the reduction, per-wavefront 32x32 staging tiles
     // (row stride CS) for the vectorised result stores afterwards
     constexpr int AB_FLOATS = 2 * BK * (BM + BN);
-    constexpr int C_FLOATS = (NT / 64) * kStageFloats;
-    __shared__ __attribute__((aligned(16))) float smem[AB_FLOATS > C_FLOATS ? AB_FLOATS : C_FLOATS];
+    // and, behind those, the partial blocks of the wavefront copies wk > 0
+    constexpr int C_FLOATS = WM * WN * kStageFloats;
+    constexpr int RED_FLOATS = (WK - 1) * WM * WN * TM * TN * 16 * 64;
+    __shared__ __attribute__((aligned(16))) float smem[AB_FLOATS > C_FLOATS + RED_FLOATS ? AB_FLOATS : C_FLOATS + RED_FLOATS];
     float (*As)[BK][BM] = reinterpret_cast<float (*)[BK][BM]>(smem);
     float (*Bs)[BK][BN] = reinterpret_cast<float (*)[BK][BN]>(smem + 2 * BK * BM);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave % WM, wn = wave / WM;
+    const int wmn = wave % (WM * WN), wk = wave / (WM * WN);
+    const int wm = wmn % WM, wn = wmn / WM;
 
     const int splitk = p.splitk > 1 ? p.splitk : 1;
     const int wg = xcd_remap((int)blockIdx.x, total * splitk);
@@ -322,18 +332,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
             if (c + PF < nchunks) load_global(u, (ch0 + c + PF) * BK);
             // operands of step kk + 2 are read from LDS while the MFMAs of step kk run
             float av[2][TM], bv[2][TN];
+            const int k0 = wk * KW + lrow;    // this wavefront's rows of the chunk
 #pragma unroll
-            for (int i = 0; i < TM; ++i) av[0][i] = As[buf][lrow][am + i * 32];
+            for (int i = 0; i < TM; ++i) av[0][i] = As[buf][k0][am + i * 32];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bv[0][j] = Bs[buf][lrow][bn + j * 32];
+            for (int j = 0; j < TN; ++j) bv[0][j] = Bs[buf][k0][bn + j * 32];
 #pragma unroll
-            for (int kk = 0; kk < BK; kk += 2) {
+            for (int kk = 0; kk < KW; kk += 2) {
                 const int cur = (kk >> 1) & 1, nxt = cur ^ 1;
-                if (kk + 2 < BK) {
+                if (kk + 2 < KW) {
 #pragma unroll
-                    for (int i = 0; i < TM; ++i) av[nxt][i] = As[buf][kk + 2 + lrow][am + i * 32];
+                    for (int i = 0; i < TM; ++i) av[nxt][i] = As[buf][k0 + kk + 2][am + i * 32];
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) bv[nxt][j] = Bs[buf][kk + 2 + lrow][bn + j * 32];
+                    for (int j = 0; j < TN; ++j) bv[nxt][j] = Bs[buf][k0 + kk + 2][bn + j * 32];
                 }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -346,10 +357,35 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f32_kernel(GemmProblem p, i
         }
     }
 
+    // ---- the wavefront copies along the reduction add their blocks into copy 0 (fixed order: same bits every run)
+    if constexpr (WK > 1) {
+        float* red = smem + C_FLOATS;         // [wk - 1][wmn][tile][register][lane]; the operands are dead (barrier above)
+        if (wk > 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        red[((((wk - 1) * (WM * WN) + wmn) * (TM * TN) + i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+        }
+        __syncthreads();
+        if (wk > 0) return;
+#pragma unroll
+        for (int w = 1; w < WK; ++w)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[i][j][r] += red[((((w - 1) * (WM * WN) + wmn) * (TM * TN) + i * TN + j) * 16 + r) * 64 + lane];
+    }
+
     // ---- results (or this slice's partial results) to memory
     const TileDest dest = tile_dest(p, b, split, splitk, ldc);
     store_tiles<TM, TN>(acc, dest, p.M, p.Ncols, m0 + wm * (BM / WM), n0 + wn * (BN / WN), lane,
-                        smem + wave * kStageFloats, vecD);
+                        smem + wmn * kStageFloats, vecD);
 }
 
 // Adds the split-K slices P[split][batch][M][ldc] in slice order, applies the bias and writes D.
@@ -412,7 +448,7 @@ Extents operand_extents(const GemmProblem& p)
     return e;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int PF = 1, bool BUF = true>
+template <int BM, int BN, int BK, int WM, int WN, int PF = 1, bool BUF = true, int WK = 1>
 hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
 {
     const int tilesM = (p.M + BM - 1) / BM;
@@ -429,17 +465,17 @@ hipError_t launch_cfg(const GemmProblem& p, bool vec, hipStream_t s)
     }
     const Extents ex = operand_extents(p);
     if (BUF && !ex.narrow) return hipErrorNotSupported;       // the caller falls back to the 64-bit loader
-    const dim3 grid((unsigned)(total * splitk)), block(WM * WN * 64);
+    const dim3 grid((unsigned)(total * splitk)), block(WM * WN * WK * 64);
     const int vecD = result_rows_vectorisable(p);
     const int ldc = gemm_splitk_ldc(p);
     if (p.gather)
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 2, PF, BUF, WK>), grid, block, 0, s, p, tilesM, tilesN,
                            (int)total, ex.a_bytes, ex.b_bytes, vecD, ldc);
     else if (vec)
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 1, PF, BUF, WK>), grid, block, 0, s, p, tilesM, tilesN,
                            (int)total, ex.a_bytes, ex.b_bytes, vecD, ldc);
     else
-        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0, PF, BUF>), grid, block, 0, s, p, tilesM, tilesN,
+        hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, BK, WM, WN, 0, PF, BUF, WK>), grid, block, 0, s, p, tilesM, tilesN,
                            (int)total, ex.a_bytes, ex.b_bytes, vecD, ldc);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess || splitk == 1) return e;
@@ -474,6 +510,13 @@ const Variant kVariants[] = {
     {"128x128x16_w2x2_pf2", launch_cfg<128, 128, 16, 2, 2, 2>, 128, 128, 16},
     {"256x128x16_w4x2_pf2", launch_cfg<256, 128, 16, 4, 2, 2>, 256, 128, 16},
     {"128x128x32_w4x2_pf2", launch_cfg<128, 128, 32, 4, 2, 2>, 128, 128, 32},
+    // small output tiles with the wavefronts of a workgroup spread along the reduction (k<WK>): four times the
+    // workgroups of a 64 x 64 tile for outputs too small to fill the chip otherwise
+    {"32x32x32_k4", launch_cfg<32, 32, 32, 1, 1, 1, true, 4>, 32, 32, 32},
+    {"32x32x32_k4_pf2", launch_cfg<32, 32, 32, 1, 1, 2, true, 4>, 32, 32, 32},
+    {"32x32x64_k4_pf2", launch_cfg<32, 32, 64, 1, 1, 2, true, 4>, 32, 32, 64},
+    {"32x64x32_w1x2k2_pf2", launch_cfg<32, 64, 32, 1, 2, 2, true, 2>, 32, 64, 32},
+    {"64x32x32_w2x1k2_pf2", launch_cfg<64, 32, 32, 2, 1, 2, true, 2>, 64, 32, 32},
 };
 constexpr int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 }  // namespace
