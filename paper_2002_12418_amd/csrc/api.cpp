@@ -719,7 +719,7 @@ int mnn_measure_device_peaks(void* stream, mnn_device_peaks* out)
         double ms = 0.0;
         if ((rc = timed(3, [&] { return launch_mfma_issue(d, wgs, iters, s); }, &ms))) break;
         m.mfma_f32_flops = (double)wgs * 4 * (4.0 * iters) * (2.0 * 32 * 32 * 2) / (ms * 1e-3);
-        if ((rc = timed(10, [&] { return launch_stream_copy(b, d, copy_bytes / 4, cus * 16, s); }, &ms))) break;
+        if ((rc = timed(10, [&] { return launch_stream_copy(b, d, copy_bytes / 4, s); }, &ms))) break;
         m.copy_bytes_per_s = 2.0 * (double)copy_bytes / (ms * 1e-3);
     } while (false);
     if (e0) (void)hipEventDestroy(e0);

@@ -128,8 +128,8 @@ hipError_t launch_strassen_combine(const StrassenView& v, const float* src, int 
 hipError_t launch_weight_transpose(const float* w, float* Wt, int K, int R, int ldk, hipStream_t s);
 
 // Device-rate probes: `workgroups` x 4 waves each issuing 4*iters fp32 32x32x2 matrix-core instructions
-// (out: workgroups*256 floats), and a 16-byte grid-stride copy of n_floats (multiple of 4, 16-byte aligned).
+// (out: workgroups*256 floats), and a 16-byte-per-lane copy of n_floats (multiple of 4, 16-byte aligned).
 hipError_t launch_mfma_issue(float* out, int workgroups, int iters, hipStream_t s);
-hipError_t launch_stream_copy(const float* src, float* dst, size_t n_floats, int workgroups, hipStream_t s);
+hipError_t launch_stream_copy(const float* src, float* dst, size_t n_floats, hipStream_t s);
 
 }  // namespace mnnconv
