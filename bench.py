@@ -51,7 +51,8 @@ def stage_work(layer, scheme, info, mnn):
 
 def recorded_traffic(cfg, kernel_desc):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary
-    (profiles/dominant_kernel_traffic.txt; counters cannot be read from inside this process).  None unless that file
+    (profiles/dominant_kernel_traffic.txt, already scaled by the readings of the copy probe; counters cannot be read
+    from inside this process).  None unless that file
     has a line for this workload whose layer and scheme are those of the kernel found dominant in this very run."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "dominant_kernel_traffic.txt")
 
@@ -314,9 +315,6 @@ def main():
     ap.add_argument("--plan-file", type=str, default="",
                     help="pre-inference cache: loaded before planning if the file exists, written after planning. "
                          "A second run with the same file launches no planner kernels (clean profiles)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="after the timed region, launch one plain 256 MiB device copy: a kernel of known traffic "
-                         "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of the same run can be scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); it has no multi-GPU path", file=sys.stderr)
@@ -436,13 +434,6 @@ def main():
                                     for b in (1, 32)]
     if args.plan_file:
         mnn.cache_save(args.plan_file)
-    if args.calibrate_copy:
-        n = 256 * 1024 * 1024 // 4
-        src = torch.rand(n, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        out["calibration_copy_bytes"] = {"read": n * 4, "write": n * 4}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers)
     print(json.dumps(out))

@@ -132,18 +132,8 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg
             }
         }
     }
-    // t = B^T d
-    float t[A][A];
-#pragma unroll
-    for (int i = 0; i < A; ++i)
-#pragma unroll
-        for (int j = 0; j < A; ++j) {
-            float acc = 0.f;
-#pragma unroll
-            for (int a = 0; a < A; ++a) acc = fmaf(bt.v[i][a], d[a][j], acc);
-            t[i][j] = acc;
-        }
-    // v = t B,  v[i][j] = sum_b t[i][b] B^T[j][b]
+    // v = B^T d B, one row of t = B^T d at a time: row i of v needs row i of t only, so t never exists as a
+    // whole and the kernel stays below 96 registers (five wavefronts per SIMD instead of three at alpha = 8).
     // element (a = i, b = j): row layout V[(i*A + j)][c][p]; blocked layout Vb[j][c/4][i][p/16][c%4][p%16]
     long long stride_i, stride_j;
     float* vp;
@@ -156,15 +146,24 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg
         stride_i = stride_j * A;
         vp = V + (long long)c * g.ldp + p;
     }
-#pragma unroll
-    for (int i = 0; i < A; ++i)
+#pragma unroll 1
+    for (int i = 0; i < A; ++i) {
+        float t[A];
 #pragma unroll
         for (int j = 0; j < A; ++j) {
             float acc = 0.f;
 #pragma unroll
-            for (int b = 0; b < A; ++b) acc = fmaf(t[i][b], bt.v[j][b], acc);
+            for (int a = 0; a < A; ++a) acc = fmaf(bt.v[i][a], d[a][j], acc);
+            t[j] = acc;
+        }
+#pragma unroll
+        for (int j = 0; j < A; ++j) {
+            float acc = 0.f;
+#pragma unroll
+            for (int b = 0; b < A; ++b) acc = fmaf(t[b], bt.v[j][b], acc);
             vp[i * stride_i + j * stride_j] = acc;
         }
+    }
 }
 
 // ---------------------------------------------------------------- output: y = A^T m A + bias
