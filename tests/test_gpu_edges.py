@@ -131,3 +131,42 @@ def test_point_scale_per_alpha_lowers_the_error_of_the_largest_tiles():
             outs.append(plan.run(xd, wd, bd).clone())
     torch.cuda.synchronize()
     assert torch.equal(outs[0], outs[1])
+
+
+DEGENERATE = [
+    ConvLayer("all_ones", 1, 1, 1, 1, 1, 1, 1, 1, 0, 1, (-1.0, 1.0), BASE_SEED + 851),              # a single multiply-add
+    ConvLayer("output_1x1", 2, 5, 3, 3, 4, 3, 3, 1, 0, 1, (-1.0, 1.0), BASE_SEED + 852),             # kernel = image
+    ConvLayer("one_row", 2, 6, 1, 37, 5, 1, 3, 1, (0, 1), 1, (-1.0, 1.0), BASE_SEED + 853),           # H = 1, 1x3 kernel
+    ConvLayer("one_column", 1, 4, 29, 1, 7, 5, 1, 1, (2, 0), 1, (-1.0, 1.0), BASE_SEED + 854),        # W = 1, 5x1 kernel
+    ConvLayer("deep_tiny", 1, 2048, 4, 4, 8, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 855),            # long reduction, 16 outputs per channel
+    ConvLayer("wide_out_tiny", 1, 3, 5, 5, 1500, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 856),        # many output channels
+    ConvLayer("many_images", 300, 3, 5, 5, 5, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 857),           # batch much larger than the image
+    ConvLayer("pad_only_border", 1, 3, 2, 2, 3, 3, 3, 1, 2, 1, (-1.0, 1.0), BASE_SEED + 858),         # most taps fall on padding
+    ConvLayer("stride_beyond_image", 2, 4, 9, 9, 3, 3, 3, 7, 1, 1, (-1.0, 1.0), BASE_SEED + 859),     # stride larger than the kernel
+    ConvLayer("k9_direct", 1, 3, 20, 20, 4, 9, 9, 1, 4, 1, (-1.0, 1.0), BASE_SEED + 860),             # more taps than the Winograd path takes
+    ConvLayer("pw_one_pixel", 7, 33, 1, 1, 65, 1, 1, 1, 0, 1, (0.0, 1.0), BASE_SEED + 861),           # 1x1 kernel on 1x1 images
+]
+
+
+@pytest.mark.parametrize("layer", DEGENERATE, ids=lambda l: l.name)
+def test_degenerate_shapes_every_scheme(layer):
+    """Shapes at the ends of the ranges: one element, one row or column, output 1 x 1, reductions and channel counts far
+    larger than the image, a batch far larger than the image, taps mostly on padding; every admissible scheme and the
+    planner's own choice against the oracle."""
+    m = mnn()
+    x, w, b = draw(layer)
+    ref = oracle.conv2d(x, w, b, stride=layer.stride, pad=layer.pad, dil=layer.dil)
+    xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+    cases = all_forced(m, layer) + [(None, None)]
+    assert len(cases) >= 2
+    for s, opt in cases:
+        print(f"[case] {layer.name} {s.label(layer.k_long) if s else 'planner'}", flush=True)
+        m.cache_clear()
+        with m.ConvPlan.for_layer(layer, options=opt) as plan:
+            y = torch.full(plan.out_shape, float("nan"), dtype=torch.float32, device="cuda")
+            plan.run(xd, wd, bd, y)
+            torch.cuda.synchronize()
+            chosen = plan.scheme
+        got = y.cpu().numpy()
+        assert got.shape == ref.shape and np.isfinite(got).all()
+        assert oracle.error_ratio(got, ref) <= tol_for(chosen, layer.k_long, m), (layer.name, chosen.label(layer.k_long))
