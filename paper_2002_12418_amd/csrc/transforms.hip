@@ -19,6 +19,9 @@ constexpr int kMaxK = 7;   // largest kernel size with a Winograd path
 // ---------------------------------------------------------------- filter: U = G w G^T
 struct FilterMat { float g[kMaxAlphaT][kMaxK]; };
 
+// KT = taps per axis.  The rows of G are walked in loops that stay rolled (alpha is a run-time value) while every
+// array index is a compile-time constant, so the kernel weights, one row of G w and nothing else live in registers.
+template <int KT>
 __global__ __launch_bounds__(256) void filter_transform_kernel(WinoGeom g, FilterMat gm,
                                                                const float* __restrict__ w,
                                                                float* __restrict__ U)
@@ -27,30 +30,36 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(WinoGeom g, Filte
     if (idx >= (long long)g.K * g.C) return;
     const int kk = (int)(idx % g.K);
     const int c = (int)(idx / g.K);
-    const int k = g.k, a = g.alpha;
-    const float* wp = w + ((long long)kk * g.C + c) * k * k;
-    float wl[kMaxK][kMaxK];
-    for (int r = 0; r < k; ++r)
-        for (int s = 0; s < k; ++s) wl[r][s] = wp[r * k + s];
-    // tmp = G w  (alpha x k)
-    float tmp[kMaxAlphaT][kMaxK];
-    for (int i = 0; i < a; ++i)
-        for (int s = 0; s < k; ++s) {
+    const int a = g.alpha;
+    const float* wp = w + ((long long)kk * g.C + c) * KT * KT;
+    float wl[KT][KT];
+#pragma unroll
+    for (int r = 0; r < KT; ++r)
+#pragma unroll
+        for (int s = 0; s < KT; ++s) wl[r][s] = wp[r * KT + s];
+#pragma unroll 1
+    for (int i = 0; i < a; ++i) {
+        // row i of G w  (k values)
+        float row[KT];
+#pragma unroll
+        for (int s = 0; s < KT; ++s) {
             float acc = 0.f;
-            for (int r = 0; r < k; ++r) acc = fmaf(gm.g[i][r], wl[r][s], acc);
-            tmp[i][s] = acc;
+#pragma unroll
+            for (int r = 0; r < KT; ++r) acc = fmaf(gm.g[i][r], wl[r][s], acc);
+            row[s] = acc;
         }
-    // U = tmp G^T  (alpha x alpha)
-    for (int i = 0; i < a; ++i)
+        // row i of U = (G w) G^T
+#pragma unroll 1
         for (int j = 0; j < a; ++j) {
             float acc = 0.f;
-            for (int s = 0; s < k; ++s) acc = fmaf(tmp[i][s], gm.g[j][s], acc);
-            const int xi = i * a + j;
+#pragma unroll
+            for (int s = 0; s < KT; ++s) acc = fmaf(row[s], gm.g[j][s], acc);
             if (g.blocked)   // Ub[b = j][c/4][a = i][k/16][c%4][k%16]
                 U[(((((long long)j * g.cchunks + (c >> 2)) * a + i) * g.kg + (kk >> 4)) << 6) + ((c & 3) << 4) + (kk & 15)] = acc;
             else
-                U[((long long)xi * g.C + c) * g.ldk + kk] = acc;
+                U[((long long)(i * a + j) * g.C + c) * g.ldk + kk] = acc;
         }
+    }
 }
 
 // 16- and 8-byte loads at 4-byte alignment (global memory takes them at any dword alignment)
@@ -320,7 +329,12 @@ hipError_t launch_filter_transform(const WinoGeom& g, const float* G, const floa
         for (int j = 0; j < kMaxK; ++j) m.g[i][j] = (i < g.alpha && j < g.k) ? G[i * g.k + j] : 0.f;
     const long long total = (long long)g.K * g.C;
     const unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(filter_transform_kernel, dim3(blocks), dim3(256), 0, s, g, m, w, U);
+    switch (g.k) {
+#define MNN_FILTER(KT_) case KT_: hipLaunchKernelGGL(filter_transform_kernel<KT_>, dim3(blocks), dim3(256), 0, s, g, m, w, U); break;
+        MNN_FILTER(2) MNN_FILTER(3) MNN_FILTER(4) MNN_FILTER(5) MNN_FILTER(6) MNN_FILTER(7)
+#undef MNN_FILTER
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
