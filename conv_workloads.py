@@ -180,7 +180,10 @@ def small_parity_layers() -> List[ConvLayer]:
         L(14, "rect_7x1_same", 2, 6, 17, 13, 9, 7, 1, 1, (3, 0)),
         L(15, "rect_1x3_same", 2, 10, 9, 22, 5, 1, 3, 1, (0, 1)),
         L(16, "rect_5x1_nopad", 1, 3, 23, 6, 4, 5, 1, 1, 0),
-        L(17, "rect_3x5_direct_only", 1, 4, 10, 12, 3, 3, 5, 1, (1, 2)),
+        L(17, "rect_3x5_same", 1, 4, 10, 12, 3, 3, 5, 1, (1, 2)),
+        L(18, "rect_5x2_nopad", 2, 7, 14, 9, 6, 5, 2, 1, 0),
+        L(19, "rect_2x7_pad", 1, 5, 11, 19, 9, 2, 7, 1, (1, 2)),
+        L(20, "rect_4x3_ragged", 2, 9, 13, 15, 10, 4, 3, 1, (2, 1)),
     ]
 
 

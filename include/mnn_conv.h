@@ -5,8 +5,9 @@
  * (arXiv 2002.12418):
  *   - pre-inference scheme selection per layer shape        (Section 3.2)
  *   - Winograd convolution F(n x n, k x k) with generated
- *     transform matrices; kernels with one row or column
- *     (1 x k, k x 1) as F(1 x n, 1 x k) / F(n x 1, k x 1)    (Section 3.3.1)
+ *     transform matrices; kernels that are not square with
+ *     one matrix set per axis: 1 x k, k x 1 as F(1 x n, 1 x k) /
+ *     F(n x 1, k x 1), k_h x k_w as F(n x n, k_h x k_w)      (Section 3.3.1)
  *   - k = 1 convolution as one large matrix multiplication  (Sections 3.2 (1), 3.3.2)
  *   - sliding-window (direct) convolution as the fallback   (Section 3.2 (1))
  *
@@ -130,9 +131,10 @@ typedef struct {
     int32_t ldp, ldk;         /* leading dimensions of V/M rows and of U rows             */
     int32_t kg, pg;           /* fused variants: allocated 16-wide groups along c_out and along P */
     int32_t h_out, w_out;
-    int32_t alpha_w, tile_n_w; /* kernels with one row or column (1 x k, k x 1): alpha and tile_n describe the H axis,
-                                  these the W axis; the axis with a single tap has alpha = tile_n = 1 and U, V, M hold
-                                  alpha * alpha_w positions.  Equal to alpha, tile_n for square kernels. */
+    int32_t alpha_w, tile_n_w; /* kernels that are not square: alpha and tile_n describe the H axis, these the W axis
+                                  (alpha = tile_n + k_h - 1, alpha_w = tile_n_w + k_w - 1); an axis with a single tap
+                                  has alpha = tile_n = 1; U, V, M hold alpha * alpha_w positions.  Equal to alpha,
+                                  tile_n for square kernels. */
 } mnn_plan_info;
 
 /* Fills *opt with the defaults listed above.  Host. */
@@ -140,10 +142,10 @@ int mnn_conv_options_default(mnn_conv_options* opt);
 
 /*
  * Pre-inference for one layer (Section 3.2): validates the shape, enumerates the
- * candidate schemes (k = 1, stride 1, pad 0 -> GEMM; stride or dilation != 1, or a
- * kernel that is neither square nor a single row or column -> sliding window only;
- * otherwise sliding window and every F(n,k) with n >= 2 and n + k - 1 <= alpha_max,
- * k the long side of the kernel), and unless a scheme is forced
+ * candidate schemes (k = 1, stride 1, pad 0 -> GEMM; stride or dilation != 1, or more
+ * than 7 taps on an axis -> sliding window only; otherwise sliding window and every
+ * F(n,k) with n >= 2 and n + k - 1 <= alpha_max, k the long side of the kernel -- at most
+ * 8 when the kernel has several taps on both axes and is not square), and unless a scheme is forced
  * or cached, times every candidate on the device with scratch tensors and
  * keeps the fastest (ties: smaller alpha).  Allocates the chosen scheme's
  * workspace.  `stream` is used for the timing launches and is synchronised.

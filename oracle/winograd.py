@@ -17,10 +17,10 @@ Takes Section 3.3.1 in its own order and notation:
      (item (2) of that section: "Hadamard product -> matrix multiplication");
   5. Y = A^T M A per (output channel, tile), plus the bias, clipped to H_o x W_o.
 
-A kernel with a single row or column (1 x k, k x 1) takes the same formula with one matrix set per axis:
-the generated F(n, k) matrices along the long side and, along the side with one tap, the trivial F(1, 1)
-(all three matrices are the 1 x 1 identity), i.e. U = G_h W G_w^T, V = B_h^T X B_w, Y = A_h^T M A_w with
-n_h x n_w output blocks.
+A kernel that is not square takes the same formula with one matrix set per axis, U = G_h W G_w^T,
+V = B_h^T X B_w, Y = A_h^T M A_w with n_h x n_w output blocks: along a side with k > 1 taps the generated
+F(n, k) matrices, along a side with one tap (1 x k, k x 1 kernels) the trivial F(1, 1), whose three matrices
+are the 1 x 1 identity.
 
 Stride 1, dilation 1 only (the paper gives no Winograd form for anything
 else).  The matrices come from oracle.cook_toom and are widened to float64.
@@ -44,12 +44,12 @@ def winograd_conv2d(x: np.ndarray, w: np.ndarray, b: Optional[np.ndarray], n: in
     N, C, H, W = x.shape
     K, C2, kh, kw = w.shape
     assert C == C2
-    assert kh == kw or kh == 1 or kw == 1, "square kernels, or kernels with one row or column"
+    assert kh > 1 or kw > 1, "a 1 x 1 kernel has no Winograd form"
     ph, pw = (pad, pad) if np.isscalar(pad) else pad
 
     def axis(k_axis):
         """(n, alpha, A^T, G, B^T) of one axis: F(n, k) along a side with k > 1 taps, the identity for one tap."""
-        if k_axis == 1 and kh != kw:
+        if k_axis == 1:
             one = np.ones((1, 1), dtype=np.float64)
             return 1, 1, one, one, one
         mats = cook_toom.matrices(n, k_axis, f)

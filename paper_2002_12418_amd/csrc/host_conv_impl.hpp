@@ -80,22 +80,27 @@ struct Impl {
             return fail(MNN_E_UNSUPPORTED, "the fused Winograd kernels multiply in fp32 only");
         if (s.kind == MNN_SCHEME_WINOGRAD) {
             if (!winograd_admissible(L))
-                return fail(MNN_E_UNSUPPORTED, "Winograd needs a square kernel >= 2 (or 1 x k / k x 1), stride 1, dilation 1");
+                return fail(MNN_E_UNSUPPORTED, "Winograd needs a kernel with more than one tap, stride 1, dilation 1");
             rect = winograd_rect(L);
             const int n = s.tile_n, k = wino_k(L);
-            if (!winograd_kernels_available(n, k))
-                return fail(MNN_E_UNSUPPORTED, "F(%d,%d) is outside the built range (n 2..8, k 2..7, alpha <= %d)", n, k, kMaxAlphaT);
-            WinogradMatrices gen, unit;
+            if (!wino_tile_available(L, n))
+                return fail(MNN_E_UNSUPPORTED, "F(%d,.) is outside the built range for a %d x %d kernel (n 2..8, k 2..7, alpha <= %d; "
+                            "alpha <= 8 with several taps on both axes)", n, sh.kh, sh.kw, kMaxAlphaT);
+            // one matrix set per axis; an axis with a single tap keeps the 1 x 1 identity.
             // f = 0: the scale with the least fp32 error for this alpha.  Up to alpha = 8 that is the paper's 0.5;
             // for 9 and 10 points spaced 0.425 apart bring the error down 3-5x (points further out blow up G, points
             // closer together blow up B^T).
-            const double f = o.point_scale_f > 0.f ? (double)o.point_scale_f : (n + k - 1 >= 9 ? 0.425 : 0.5);
-            if (!generate_winograd(n, k, f, &gen))
+            auto axis_matrices = [&](int k_axis, WinogradMatrices* out) -> bool {
+                if (k_axis == 1) {
+                    out->n = out->k = out->alpha = 1;
+                    out->AT.assign(1, 1.f); out->G.assign(1, 1.f); out->BT.assign(1, 1.f);
+                    return true;
+                }
+                const double f = o.point_scale_f > 0.f ? (double)o.point_scale_f : (n + k_axis - 1 >= 9 ? 0.425 : 0.5);
+                return generate_winograd(n, k_axis, f, out);
+            };
+            if (!axis_matrices(sh.kh, &mats) || !axis_matrices(sh.kw, &mats_w))
                 return fail(MNN_E_UNSUPPORTED, "generator rejected F(%d,%d)", n, k);
-            unit.n = unit.k = unit.alpha = 1;
-            unit.AT.assign(1, 1.f); unit.G.assign(1, 1.f); unit.BT.assign(1, 1.f);
-            mats = (rect && sh.kh == 1) ? unit : gen;
-            mats_w = (rect && sh.kw == 1) ? unit : gen;
             wg.N = sh.n; wg.C = sh.c_in; wg.H = sh.h; wg.W = sh.w; wg.K = sh.c_out;
             wg.Ho = L.Ho; wg.Wo = L.Wo; wg.pad_h = L.g.pad_h; wg.pad_w = L.g.pad_w;
             wg.n = mats.n; wg.k = mats.k; wg.alpha = mats.alpha;
@@ -106,8 +111,8 @@ struct Impl {
             wg.P = (int)P; wg.ldp = round_up(wg.P, 4); wg.ldk = ldk;
             const size_t a2 = (size_t)wg.alpha * wg.alpha_w;
             if (rect && s.variant != MNN_WINO_UNFUSED)
-                return fail(MNN_E_UNSUPPORTED, "kernels with one row or column have no fused variant");
-            if (!wino_variant_available(n, k, s.variant))
+                return fail(MNN_E_UNSUPPORTED, "kernels that are not square have no fused variant");
+            if (!rect && !wino_variant_available(n, k, s.variant))
                 return fail(MNN_E_UNSUPPORTED, "Winograd variant %d is not available for F(%d,%d)", s.variant, n, k);
             int rc;
             if (s.variant != MNN_WINO_UNFUSED) {

@@ -96,16 +96,28 @@ bool is_pointwise(const Layer& L)
     return L.s.kh == 1 && L.s.kw == 1 && L.g.stride_h == 1 && L.g.stride_w == 1 && L.g.pad_h == 0 && L.g.pad_w == 0;
 }
 
-// kernels with a single row or column (1 x k, k x 1, k >= 2): one-dimensional Winograd along the long axis
+// kernels that are not square: a single row or column (1 x k, k x 1: one-dimensional Winograd along the long axis)
+// or several taps on both axes (k_h x k_w: one generated matrix set per axis, n x n output tiles)
 bool winograd_rect(const Layer& L)
 {
-    return (L.s.kh == 1) != (L.s.kw == 1);
+    return L.s.kh != L.s.kw;
 }
+
+// output tile extent along an axis with k taps when the scheme's tile is n
+int wino_axis_n(int k, int n) { return k == 1 ? 1 : n; }
 
 bool winograd_admissible(const Layer& L)
 {
     const bool shape_ok = (L.s.kh == L.s.kw && L.s.kh >= 2) || winograd_rect(L);
     return shape_ok && L.g.stride_h == 1 && L.g.stride_w == 1 && L.g.dil_h == 1 && L.g.dil_w == 1;
+}
+
+// whether the transform kernels of F(n, .) exist for this layer's kernel shape
+bool wino_tile_available(const Layer& L, int n)
+{
+    if (winograd_rect(L))
+        return winograd_rect_kernels_available(wino_axis_n(L.s.kh, n), L.s.kh, wino_axis_n(L.s.kw, n), L.s.kw);
+    return winograd_kernels_available(n, L.s.kh);
 }
 
 int wino_k(const Layer& L) { return L.s.kh > L.s.kw ? L.s.kh : L.s.kw; }    // taps along the transformed axis
@@ -176,7 +188,7 @@ std::vector<mnn_scheme> enumerate(const Layer& L, const mnn_conv_options& o)
         const int k = wino_k(L);
         for (int n = 2; n + k - 1 <= o.alpha_max; ++n) {
             if (winograd_rect(L)) {          // transforms and GEMM as separate kernels only
-                if (winograd_kernels_available(n, k)) {
+                if (wino_tile_available(L, n)) {
                     out.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, MNN_GEMM_FP32, MNN_WINO_UNFUSED));
                     if (o.allow_bf16) out.push_back(make_scheme(MNN_SCHEME_WINOGRAD, n, MNN_GEMM_BF16X3, MNN_WINO_UNFUSED));
                 }

@@ -18,10 +18,10 @@ std::vector<KernelWork> scheme_kernels(const Layer& L, const mnn_scheme& s)
     const double in_b = 4.0 * N * C * H * W, out_b = 4.0 * N * K * Ho * Wo, w_b = 4.0 * K * C * L.s.kh * L.s.kw;
     std::vector<KernelWork> v;
     if (s.kind == MNN_SCHEME_WINOGRAD) {
-        const bool rect = winograd_rect(L);
-        const double n = s.tile_n, k = wino_k(L), a = n + k - 1;
-        const double nh = (rect && L.s.kh == 1) ? 1 : n, nw = (rect && L.s.kw == 1) ? 1 : n;
-        const double ah = (rect && L.s.kh == 1) ? 1 : a, aw = (rect && L.s.kw == 1) ? 1 : a;
+        const double n = s.tile_n;
+        const double nh = wino_axis_n(L.s.kh, s.tile_n), nw = wino_axis_n(L.s.kw, s.tile_n);
+        const double ah = nh + L.s.kh - 1, aw = nw + L.s.kw - 1;
+        (void)n;
         const double P = N * std::ceil(Ho / nh) * std::ceil(Wo / nw), a2 = ah * aw;
         v.push_back(KernelWork{2.0 * (ah * ah * aw + ah * aw * aw) * C * P, in_b + 4.0 * a2 * C * P});
         if (s.variant == MNN_WINO_UNFUSED) {

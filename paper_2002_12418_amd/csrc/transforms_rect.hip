@@ -1,11 +1,12 @@
-// One-dimensional Winograd transforms for kernels with a single row or column (1 x k and k x 1), the
-// rectangular case of Section 3.3.1 of the MNN paper ("kernels of any size"): the generated F(n, k) matrices
-// act along the long axis of the kernel, the other axis is left alone (its matrices are the 1 x 1 identity):
+// Winograd transforms for kernels that are not square, the rectangular case of Section 3.3.1 of the MNN paper
+// ("kernels of any size"): every axis has its own generated matrix set,
 //   U = G_h w G_w^T,   V = B_h^T d B_w,   Y = A_h^T [ sum_c U (.) V ] A_w,
-// with alpha_h x alpha_w Winograd-domain positions, one of the two equal to 1.
+// with alpha_h x alpha_w Winograd-domain positions.  Along an axis with a single tap (1 x k, k x 1 kernels) the
+// matrices are the 1 x 1 identity and the transform is one-dimensional; with several taps on both axes
+// (k_h x k_w, k_h != k_w) the output tile is n x n and alpha_h = n + k_h - 1, alpha_w = n + k_w - 1.
 //
 // Same mapping as the square kernels: one lane per (channel, tile), consecutive lanes are consecutive tiles,
-// so stores of V and loads of M are contiguous across the wavefront.  A tile is 1 x n (n x 1) outputs.
+// so stores of V and loads of M are contiguous across the wavefront.
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
 
@@ -13,6 +14,7 @@ namespace mnnconv {
 namespace {
 
 constexpr int kMaxK = 7;
+constexpr int kMaxMixedAlpha = 8;      // k_h x k_w kernels with several taps on both axes are built up to alpha = 8
 
 struct RectFilterMat { float gh[kMaxAlphaT][kMaxK], gw[kMaxAlphaT][kMaxK]; };
 
@@ -171,7 +173,8 @@ bool rect_geom_ok(const WinoGeom& g)
 {
     if (g.N <= 0 || g.C <= 0 || g.H <= 0 || g.W <= 0 || g.K <= 0 || g.blocked) return false;
     if (!axis_ok(g.n, g.k, g.alpha) || !axis_ok(g.nw, g.kw, g.alpha_w)) return false;
-    if ((g.k == 1) == (g.kw == 1)) return false;                  // exactly one axis is transformed
+    if (g.k == g.kw) return false;                                // square kernels take the other kernels
+    if (g.k > 1 && g.kw > 1 && (g.n != g.nw || g.alpha > kMaxMixedAlpha || g.alpha_w > kMaxMixedAlpha)) return false;
     if (g.Ho != g.H + 2 * g.pad_h - g.k + 1 || g.Wo != g.W + 2 * g.pad_w - g.kw + 1 || g.Ho <= 0 || g.Wo <= 0) return false;
     if (g.th != (g.Ho + g.n - 1) / g.n || g.tw != (g.Wo + g.nw - 1) / g.nw) return false;
     if ((long long)g.P != (long long)g.N * g.th * g.tw) return false;
@@ -185,7 +188,9 @@ bool rect_geom_ok(const WinoGeom& g)
 
 bool winograd_rect_kernels_available(int nh, int kh, int nw, int kw)
 {
-    return axis_ok(nh, kh, nh + kh - 1) && axis_ok(nw, kw, nw + kw - 1) && ((kh == 1) != (kw == 1));
+    if (!axis_ok(nh, kh, nh + kh - 1) || !axis_ok(nw, kw, nw + kw - 1) || kh == kw) return false;
+    if (kh > 1 && kw > 1) return nh == nw && nh + kh - 1 <= kMaxMixedAlpha && nw + kw - 1 <= kMaxMixedAlpha;
+    return true;
 }
 
 hipError_t launch_filter_transform_rect(const WinoGeom& g, const float* Gh, const float* Gw, const float* w, float* U,
@@ -212,6 +217,37 @@ hipError_t launch_input_transform_rect(const WinoGeom& g, const float* BTh, cons
     if (g.alpha == A && g.alpha_w == 1) return launch_input_r<A, 1>(g, BTh, BTw, x, V, s);
     MNN_CASE(3) MNN_CASE(4) MNN_CASE(5) MNN_CASE(6) MNN_CASE(7) MNN_CASE(8) MNN_CASE(9) MNN_CASE(10)
 #undef MNN_CASE
+    // several taps on both axes: every pair of different alphas from 3 to 8
+    if (g.alpha == 3 && g.alpha_w == 4) return launch_input_r<3, 4>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 3 && g.alpha_w == 5) return launch_input_r<3, 5>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 3 && g.alpha_w == 6) return launch_input_r<3, 6>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 3 && g.alpha_w == 7) return launch_input_r<3, 7>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 3 && g.alpha_w == 8) return launch_input_r<3, 8>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 4 && g.alpha_w == 3) return launch_input_r<4, 3>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 4 && g.alpha_w == 5) return launch_input_r<4, 5>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 4 && g.alpha_w == 6) return launch_input_r<4, 6>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 4 && g.alpha_w == 7) return launch_input_r<4, 7>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 4 && g.alpha_w == 8) return launch_input_r<4, 8>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 5 && g.alpha_w == 3) return launch_input_r<5, 3>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 5 && g.alpha_w == 4) return launch_input_r<5, 4>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 5 && g.alpha_w == 6) return launch_input_r<5, 6>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 5 && g.alpha_w == 7) return launch_input_r<5, 7>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 5 && g.alpha_w == 8) return launch_input_r<5, 8>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 6 && g.alpha_w == 3) return launch_input_r<6, 3>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 6 && g.alpha_w == 4) return launch_input_r<6, 4>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 6 && g.alpha_w == 5) return launch_input_r<6, 5>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 6 && g.alpha_w == 7) return launch_input_r<6, 7>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 6 && g.alpha_w == 8) return launch_input_r<6, 8>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 7 && g.alpha_w == 3) return launch_input_r<7, 3>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 7 && g.alpha_w == 4) return launch_input_r<7, 4>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 7 && g.alpha_w == 5) return launch_input_r<7, 5>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 7 && g.alpha_w == 6) return launch_input_r<7, 6>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 7 && g.alpha_w == 8) return launch_input_r<7, 8>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 8 && g.alpha_w == 3) return launch_input_r<8, 3>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 8 && g.alpha_w == 4) return launch_input_r<8, 4>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 8 && g.alpha_w == 5) return launch_input_r<8, 5>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 8 && g.alpha_w == 6) return launch_input_r<8, 6>(g, BTh, BTw, x, V, s);
+    if (g.alpha == 8 && g.alpha_w == 7) return launch_input_r<8, 7>(g, BTh, BTw, x, V, s);
     return hipErrorInvalidValue;
 }
 
@@ -219,6 +255,80 @@ hipError_t launch_output_transform_rect(const WinoGeom& g, const float* ATh, con
                                         const float* bias, float* y, hipStream_t s)
 {
     if (!rect_geom_ok(g) || !ATh || !ATw || !M || !y) return hipErrorInvalidValue;
+    if (g.k > 1 && g.kw > 1) {
+        // n x n tiles of a k_h x k_w kernel: every (n, k_h, k_w) with both alphas up to 8
+        if (g.n == 2 && g.k == 2 && g.kw == 3) return launch_output_r<2, 2, 3, 4>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 2 && g.kw == 3) return launch_output_r<3, 3, 4, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 2 && g.kw == 3) return launch_output_r<4, 4, 5, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 5 && g.k == 2 && g.kw == 3) return launch_output_r<5, 5, 6, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 6 && g.k == 2 && g.kw == 3) return launch_output_r<6, 6, 7, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 2 && g.kw == 4) return launch_output_r<2, 2, 3, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 2 && g.kw == 4) return launch_output_r<3, 3, 4, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 2 && g.kw == 4) return launch_output_r<4, 4, 5, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 5 && g.k == 2 && g.kw == 4) return launch_output_r<5, 5, 6, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 2 && g.kw == 5) return launch_output_r<2, 2, 3, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 2 && g.kw == 5) return launch_output_r<3, 3, 4, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 2 && g.kw == 5) return launch_output_r<4, 4, 5, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 2 && g.kw == 6) return launch_output_r<2, 2, 3, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 2 && g.kw == 6) return launch_output_r<3, 3, 4, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 2 && g.kw == 7) return launch_output_r<2, 2, 3, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 3 && g.kw == 2) return launch_output_r<2, 2, 4, 3>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 3 && g.kw == 2) return launch_output_r<3, 3, 5, 4>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 3 && g.kw == 2) return launch_output_r<4, 4, 6, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 5 && g.k == 3 && g.kw == 2) return launch_output_r<5, 5, 7, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 6 && g.k == 3 && g.kw == 2) return launch_output_r<6, 6, 8, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 3 && g.kw == 4) return launch_output_r<2, 2, 4, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 3 && g.kw == 4) return launch_output_r<3, 3, 5, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 3 && g.kw == 4) return launch_output_r<4, 4, 6, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 5 && g.k == 3 && g.kw == 4) return launch_output_r<5, 5, 7, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 3 && g.kw == 5) return launch_output_r<2, 2, 4, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 3 && g.kw == 5) return launch_output_r<3, 3, 5, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 3 && g.kw == 5) return launch_output_r<4, 4, 6, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 3 && g.kw == 6) return launch_output_r<2, 2, 4, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 3 && g.kw == 6) return launch_output_r<3, 3, 5, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 3 && g.kw == 7) return launch_output_r<2, 2, 4, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 4 && g.kw == 2) return launch_output_r<2, 2, 5, 3>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 4 && g.kw == 2) return launch_output_r<3, 3, 6, 4>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 4 && g.kw == 2) return launch_output_r<4, 4, 7, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 5 && g.k == 4 && g.kw == 2) return launch_output_r<5, 5, 8, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 4 && g.kw == 3) return launch_output_r<2, 2, 5, 4>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 4 && g.kw == 3) return launch_output_r<3, 3, 6, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 4 && g.kw == 3) return launch_output_r<4, 4, 7, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 5 && g.k == 4 && g.kw == 3) return launch_output_r<5, 5, 8, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 4 && g.kw == 5) return launch_output_r<2, 2, 5, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 4 && g.kw == 5) return launch_output_r<3, 3, 6, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 4 && g.kw == 5) return launch_output_r<4, 4, 7, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 4 && g.kw == 6) return launch_output_r<2, 2, 5, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 4 && g.kw == 6) return launch_output_r<3, 3, 6, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 4 && g.kw == 7) return launch_output_r<2, 2, 5, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 5 && g.kw == 2) return launch_output_r<2, 2, 6, 3>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 5 && g.kw == 2) return launch_output_r<3, 3, 7, 4>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 5 && g.kw == 2) return launch_output_r<4, 4, 8, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 5 && g.kw == 3) return launch_output_r<2, 2, 6, 4>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 5 && g.kw == 3) return launch_output_r<3, 3, 7, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 5 && g.kw == 3) return launch_output_r<4, 4, 8, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 5 && g.kw == 4) return launch_output_r<2, 2, 6, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 5 && g.kw == 4) return launch_output_r<3, 3, 7, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 4 && g.k == 5 && g.kw == 4) return launch_output_r<4, 4, 8, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 5 && g.kw == 6) return launch_output_r<2, 2, 6, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 5 && g.kw == 6) return launch_output_r<3, 3, 7, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 5 && g.kw == 7) return launch_output_r<2, 2, 6, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 6 && g.kw == 2) return launch_output_r<2, 2, 7, 3>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 6 && g.kw == 2) return launch_output_r<3, 3, 8, 4>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 6 && g.kw == 3) return launch_output_r<2, 2, 7, 4>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 6 && g.kw == 3) return launch_output_r<3, 3, 8, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 6 && g.kw == 4) return launch_output_r<2, 2, 7, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 6 && g.kw == 4) return launch_output_r<3, 3, 8, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 6 && g.kw == 5) return launch_output_r<2, 2, 7, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 3 && g.k == 6 && g.kw == 5) return launch_output_r<3, 3, 8, 7>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 6 && g.kw == 7) return launch_output_r<2, 2, 7, 8>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 7 && g.kw == 2) return launch_output_r<2, 2, 8, 3>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 7 && g.kw == 3) return launch_output_r<2, 2, 8, 4>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 7 && g.kw == 4) return launch_output_r<2, 2, 8, 5>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 7 && g.kw == 5) return launch_output_r<2, 2, 8, 6>(g, ATh, ATw, M, bias, y, s);
+        if (g.n == 2 && g.k == 7 && g.kw == 6) return launch_output_r<2, 2, 8, 7>(g, ATh, ATw, M, bias, y, s);
+        return hipErrorInvalidValue;
+    }
     const int n = g.k == 1 ? g.nw : g.n, k = g.k == 1 ? g.kw : g.k;
 #define MNN_NK(NN, KK)                                                                                       \
     if (n == NN && k == KK) {                                                                                \

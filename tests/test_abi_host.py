@@ -82,11 +82,17 @@ def test_enumeration_rules(mnn):
     assert [(s.kind, s.variant) for s in c] == [(mnn.SCHEME_GEMM1X1, v) for v in (0, 1, 2)]
     c = mnn.enumerate_schemes(3, 19, 7, 7, 21, 1, 1)       # nothing divides: the plain product only
     assert [(s.kind, s.variant) for s in c] == [(mnn.SCHEME_GEMM1X1, 0)]
-    # stride 2 / dilation 2 / a kernel that is neither square nor a single row or column -> sliding window only
+    # stride 2 / dilation 2 -> sliding window only
     for kw in (dict(stride=2, pad=1), dict(dil=2, pad=2)):
         c = mnn.enumerate_schemes(1, 64, 56, 56, 128, 3, 3, **kw)
         assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
+    # k_h x k_w with several taps on both axes: sliding window + F(n, .) with n x n tiles while the larger alpha is <= 8
     c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 3, 5)
+    assert c[0].kind == mnn.SCHEME_DIRECT
+    assert [(s.kind, s.tile_n, s.variant) for s in c[1:]] == [(mnn.SCHEME_WINOGRAD, n, mnn.WINO_UNFUSED) for n in (2, 3, 4)]
+    c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 3, 5, options=mnn.Options(alpha_max=10))      # still alpha <= 8 for these
+    assert [s.tile_n for s in c[1:]] == [2, 3, 4]
+    c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 2, 9)                                           # more than 7 taps on an axis
     assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
     c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 1, 7, stride=(1, 2))
     assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]

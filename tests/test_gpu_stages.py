@@ -99,12 +99,18 @@ RECT_CASES = [
     (4, 1, 3, 2, 10, 9, 22, 5, (0, 1)),
     (6, 3, 1, 1, 7, 20, 5, 4, (1, 0)),
     (4, 5, 1, 1, 3, 23, 6, 4, (0, 0)),
+    # several taps on both axes
+    (2, 3, 5, 1, 4, 10, 12, 3, (1, 2)),
+    (4, 5, 2, 2, 7, 14, 9, 6, (0, 0)),
+    (2, 2, 7, 1, 5, 11, 19, 9, (1, 2)),
+    (5, 4, 3, 2, 9, 13, 15, 10, (2, 1)),
 ]
 
 
 @pytest.mark.parametrize("case", RECT_CASES)
 def test_single_row_or_column_stage_buffers(case):
-    """Kernels with one row or column: U, V, M hold alpha_h x alpha_w positions, one of the two equal to 1."""
+    """Kernels that are not square: U, V, M hold alpha_h x alpha_w positions (one of the two equal to 1 for kernels with
+    one row or column)."""
     m = mnn()
     n, kh, kw, N, C, H, W, K, pad = case
     layer = ConvLayer("t", N, C, H, W, K, kh, kw, 1, pad, 1, (-1.0, 1.0), BASE_SEED + 600 + n + 7 * kh + kw)
@@ -116,7 +122,7 @@ def test_single_row_or_column_stage_buffers(case):
     with m.ConvPlan.for_layer(layer, options=opt) as plan:
         info = plan.info
         assert (info["alpha"], info["alpha_w"]) == (ah, aw)
-        assert (info["tile_n"], info["tile_n_w"]) == ((1, n) if kh == 1 else (n, 1))
+        assert (info["tile_n"], info["tile_n_w"]) == (1 if kh == 1 else n, 1 if kw == 1 else n)
         y = plan.run(xd, wd, bd)
         torch.cuda.synchronize()
         P, ldp, ldk = info["p"], info["ldp"], info["ldk"]

@@ -73,3 +73,34 @@ def test_single_row_or_column_kernels_equal_definition(case):
     line = w[:, :, 0, :] if kh == 1 else w[:, :, :, 0]
     g = st["G_w"] if kh == 1 else st["G"]
     assert np.allclose(st["U"].reshape(max(ah, aw), K, C), np.einsum("ir,kcr->ikc", g, line), rtol=0, atol=1e-14)
+
+
+MIXED_CASES = [
+    # n, kh, kw, N, C, H, W, K, pad: several taps on both axes, kh != kw
+    (2, 3, 5, 1, 3, 10, 12, 2, (1, 2)),
+    (4, 5, 2, 2, 2, 14, 9, 3, (0, 0)),      # even taps along W, ragged tiles both ways
+    (2, 2, 7, 1, 2, 11, 19, 2, (1, 2)),
+    (5, 4, 3, 1, 3, 13, 15, 2, (2, 1)),     # n = 5: alpha 8 x 7
+    (3, 7, 4, 1, 2, 16, 9, 2, (3, 0)),      # alpha 9 x 6
+]
+
+
+@pytest.mark.parametrize("case", MIXED_CASES)
+def test_kernels_with_different_tap_counts_per_axis_equal_definition(case):
+    """k_h x k_w kernels: F(n, k_h) down the columns and F(n, k_w) along the rows is still the plain convolution, and
+    U is the two-sided transform of the kernel with the two different G matrices."""
+    n, kh, kw, N, C, H, W, K, pad = case
+    layer = ConvLayer("t", N, C, H, W, K, kh, kw, 1, pad, 1, (-1.0, 1.0), BASE_SEED + 277 + n + kh * 7 + kw)
+    x, w, b = draw(layer)
+    ref = oracle.conv2d(x, w, b, stride=1, pad=pad)
+    y, st = winograd.winograd_conv2d(x, w, b, n, pad=pad, return_stages=True)
+    assert y.shape == ref.shape
+    assert oracle.error_ratio(y, ref) < 1e-10
+    ah, aw = n + kh - 1, n + kw - 1
+    assert st["U"].shape == (ah, aw, K, C) and st["G"].shape == (ah, kh) and st["G_w"].shape == (aw, kw)
+    assert st["V"].shape == (ah, aw, C, N * (-(-layer.h_out // n)) * (-(-layer.w_out // n)))
+    # a kernel that is an outer product a (x) b transforms into the outer product (G_h a) (x) (G_w b)
+    a_vec, b_vec = np.arange(1.0, kh + 1), np.arange(1.0, kw + 1)[::-1]
+    w1 = np.broadcast_to(np.outer(a_vec, b_vec), (1, 1, kh, kw)).astype(np.float64)
+    _, st1 = winograd.winograd_conv2d(np.zeros((1, 1, H, W)), w1, None, n, pad=pad, return_stages=True)
+    assert np.allclose(st1["U"][:, :, 0, 0], np.outer(st["G"] @ a_vec, st["G_w"] @ b_vec), rtol=1e-13, atol=1e-13)
