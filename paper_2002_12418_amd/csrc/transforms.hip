@@ -178,11 +178,14 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg
 // ---------------------------------------------------------------- output: y = A^T m A + bias
 // STREAM: M is larger than the last-level cache, so this (its last) read goes past the caches instead of
 // evicting what the next kernel could still use; small M is read normally (it is still resident from the GEMM).
-template <int NT, int A, bool STREAM>
+// VEC: how a tile row is stored -- 0: one float at a time; 1: pairs (n and W_o even, 8-byte aligned base);
+// 2: one 16-byte store (n = 4, 4 | W_o, 16-byte aligned base).  A compile-time choice: with the choice made at run
+// time the unused store paths stay in the kernel and cost 10 % of its time.
+template <int NT, int A, bool STREAM, int VEC>
 __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatArg<NT, A> at,
                                                                const float* __restrict__ M,
                                                                const float* __restrict__ bias,
-                                                               float* __restrict__ y, int vec2)
+                                                               float* __restrict__ y)
 {
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (long long)g.K * g.P) return;
@@ -201,18 +204,24 @@ __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatAr
     for (int i = 0; i < NT; ++i)
 #pragma unroll
         for (int b = 0; b < A; ++b) t[i][b] = 0.f;
+    // All alpha^2 loads are issued before the first use: a wavefront then waits for memory once, not once per
+    // row of m (the kernel is bound by that latency, not by registers: 4 or 8 wavefronts per SIMD make no difference).
+    float m[A][A];
 #pragma unroll
-    for (int a = 0; a < A; ++a) {
-        float mrow[A];
+    for (int a = 0; a < A; ++a)
 #pragma unroll
-        for (int b = 0; b < A; ++b) mrow[b] = STREAM ? __builtin_nontemporal_load(mp + (long long)(a * A + b) * plane) : mp[(long long)(a * A + b) * plane];
+        for (int b = 0; b < A; ++b)
+            m[a][b] = STREAM ? __builtin_nontemporal_load(mp + (long long)(a * A + b) * plane) : mp[(long long)(a * A + b) * plane];
+    __builtin_amdgcn_sched_barrier(0);        // keep the compiler from sinking the loads between the multiply-adds
+#pragma unroll
+    for (int a = 0; a < A; ++a)
 #pragma unroll
         for (int i = 0; i < NT; ++i)
 #pragma unroll
-            for (int b = 0; b < A; ++b) t[i][b] = fmaf(at.v[i][a], mrow[b], t[i][b]);
-    }
+            for (int b = 0; b < A; ++b) t[i][b] = fmaf(at.v[i][a], m[a][b], t[i][b]);
     const float bv = bias ? bias[kk] : 0.f;
     float* yp = y + ((long long)img * g.K + kk) * g.Ho * g.Wo;
+    const bool whole_w = tx * NT + NT <= g.Wo;      // the tile does not hang over the right edge
     // A lane owns NT consecutive floats of NT output rows.  Stores of one float per lane would touch
     // 64*NT*4/64 cache lines per instruction; pairs halve the number of store instructions.
 #pragma unroll
@@ -228,19 +237,24 @@ __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatAr
         }
         if (oy >= g.Ho) continue;
         float* row = yp + (long long)oy * g.Wo + tx * NT;
-        if constexpr (NT == 4) {
-            if (vec2 == 2) {          // 16-byte aligned tile rows, no ragged column
+        if constexpr (NT == 4 && VEC == 2) {
+            {                         // 16-byte aligned tile rows, no ragged column
                 *reinterpret_cast<float4*>(row) = make_float4(o[0], o[1], o[2], o[3]);
                 continue;
             }
         }
-        if constexpr (NT % 2 == 0) {
-            if (vec2) {
+        if constexpr (NT % 2 == 0 && VEC == 1) {
+            // n and W_o even: a pair of columns lies inside the row or outside it, never across its end, so the
+            // pairs need no 4-byte fallback (with one in the same loop the compiler turns every pair of every tile into
+            // two predicated 4-byte stores: 180 instead of 156 us for F(6,3) on 128 x 128 x 256 x 16)
+            {
+                if (whole_w) {            // unconditional: the compiler joins the pairs of a row into 16-byte stores
 #pragma unroll
-                for (int j = 0; j < NT; j += 2) {
-                    const int ox = tx * NT + j;
-                    if (ox + 1 < g.Wo) *reinterpret_cast<float2*>(row + j) = make_float2(o[j], o[j + 1]);
-                    else if (ox < g.Wo) row[j] = o[j];
+                    for (int j = 0; j < NT; j += 2) *reinterpret_cast<float2*>(row + j) = make_float2(o[j], o[j + 1]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < NT; j += 2)
+                        if (tx * NT + j < g.Wo) *reinterpret_cast<float2*>(row + j) = make_float2(o[j], o[j + 1]);
                 }
                 continue;
             }
@@ -286,10 +300,20 @@ hipError_t launch_output_t(const WinoGeom& g, const float* AT, const float* M, c
     if (NT == 4 && (g.Wo % 4 == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0)) vec2 = 2;   // whole-tile float4 rows
     // 256 MB of last-level cache on this part; well above half of it nothing of M survives until it is read
     const bool stream = (double)A * A * g.K * g.ldp * sizeof(float) > 160e6;
-    if (stream)
-        hipLaunchKernelGGL((output_transform_kernel<NT, A, true>), dim3(blocks), dim3(256), 0, s, g, m, M, bias, y, vec2);
-    else
-        hipLaunchKernelGGL((output_transform_kernel<NT, A, false>), dim3(blocks), dim3(256), 0, s, g, m, M, bias, y, vec2);
+    auto launch = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, s, g, m, M, bias, y); };
+    if constexpr (NT == 4) {
+        if (vec2 == 2) {
+            if (stream) launch(output_transform_kernel<NT, A, true, 2>); else launch(output_transform_kernel<NT, A, false, 2>);
+            return hipGetLastError();
+        }
+    }
+    if constexpr (NT % 2 == 0) {
+        if (vec2) {
+            if (stream) launch(output_transform_kernel<NT, A, true, 1>); else launch(output_transform_kernel<NT, A, false, 1>);
+            return hipGetLastError();
+        }
+    }
+    if (stream) launch(output_transform_kernel<NT, A, true, 0>); else launch(output_transform_kernel<NT, A, false, 0>);
     return hipGetLastError();
 }
 
