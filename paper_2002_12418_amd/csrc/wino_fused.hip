@@ -28,6 +28,9 @@
 // of the previous chunk run; every MFMA operand is then one conflict-free
 // ds_read_b32 of 64 consecutive floats.
 #include <hip/hip_runtime.h>
+#include <map>
+#include <mutex>
+#include <utility>
 #include "kernels.hpp"
 
 namespace mnnconv {
@@ -51,7 +54,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void wino_fused_kernel(WinoGeom g,
                                                                   const float* __restrict__ Vb,
                                                                   const float* __restrict__ bias,
                                                                   float* __restrict__ y, int kblocks, int nch,
-                                                                  int vec_store)
+                                                                  int vec_store, int pb0)
 {
     constexpr int NW = WM * WN;
     constexpr int MG = WM * WTM;              // 16-row groups of the K block
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void wino_fused_kernel(WinoGeom g,
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WM, wn = wave / WM;
     const int kb = blockIdx.x % kblocks;      // K blocks fastest: neighbours share the V block
-    const int pb = blockIdx.x / kblocks;
+    const int pb = pb0 + blockIdx.x / kblocks;  // pb0: first tile block of this launch (a launch may cover a range)
 
     const float* __restrict__ Up = Ub + (long long)kb * MG * 64;
     const float* __restrict__ Vp = Vb + (long long)pb * PG * 64;
@@ -265,25 +268,42 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void wino_fused_kernel(WinoGeom g,
     }
 }
 
+// Range of one launch, in tile blocks of the configuration: [first, first + count); count < 0 = to the end.
+// resident != nullptr: only report how many workgroups of this configuration the device holds at once.
+struct FusedRange { int first = 0, count = -1; int* resident = nullptr; };
+
 template <int NT_, int K_, int WTM, int WTN, int WM, int WN, int BKG, int NS>
 hipError_t launch_fused_t(const WinoGeom& g, const float* AT, const float* Ub, const float* Vb, const float* bias,
-                          float* y, hipStream_t s)
+                          float* y, hipStream_t s, const FusedRange& r)
 {
     constexpr int A = NT_ + K_ - 1;
     constexpr int KB = WM * WTM * 16, PB = WN * WTN * 16;
+    auto kernel = wino_fused_kernel<A, NT_, WTM, WTN, WM, WN, BKG, NS>;
+    if (r.resident) {
+        int per_cu = 0, dev = 0, cus = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, WM * WN * 64, 0);
+        if (e == hipSuccess) e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        *r.resident = per_cu * cus;
+        return hipSuccess;
+    }
     // the kernel copies whole blocks and whole chunks without bounds checks: the padded extents must cover them
     const int kblocks = (g.K + KB - 1) / KB;
     const int pblocks = (g.P + PB - 1) / PB;
     if (kblocks * (KB / 16) > g.kg || pblocks * (PB / 16) > g.pg) return hipErrorInvalidValue;
     if (g.cchunks % BKG != 0 || g.cchunks * 4 < g.C) return hipErrorInvalidValue;
-    if ((long long)kblocks * pblocks >= (1ll << 31)) return hipErrorInvalidValue;
+    const int count = r.count < 0 ? pblocks - r.first : r.count;
+    if (r.first < 0 || count < 0 || r.first + count > pblocks) return hipErrorInvalidValue;
+    if (count == 0) return hipSuccess;
+    if ((long long)kblocks * count >= (1ll << 31)) return hipErrorInvalidValue;
     MatArg<NT_, A> m;
     for (int i = 0; i < NT_; ++i)
         for (int j = 0; j < A; ++j) m.v[i][j] = AT[i * A + j];
     // vector stores need every tile row start 16/8-byte aligned: W_o a multiple of n and an aligned base
     const bool vec = (NT_ == 4 || NT_ == 2) && (g.Wo % NT_ == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0);
-    hipLaunchKernelGGL((wino_fused_kernel<A, NT_, WTM, WTN, WM, WN, BKG, NS>), dim3((unsigned)(kblocks * pblocks)),
-                       dim3(WM * WN * 64), 0, s, g, m, Ub, Vb, bias, y, kblocks, g.cchunks / BKG, vec ? 1 : 0);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(kblocks * count)), dim3(WM * WN * 64), 0, s, g, m, Ub, Vb, bias, y, kblocks,
+                       g.cchunks / BKG, vec ? 1 : 0, r.first);
     return hipGetLastError();
 }
 
@@ -310,21 +330,17 @@ bool wino_fused_available(int n, int k)
 
 bool wino_fused_has_big_block(int n, int k) { return wino_fused_available(n, k) && fits_big(n, k); }
 
-// config 0: 32 channels x 32 tiles per workgroup (4 wavefronts, one 16x16 tile each);
-// config 1: 64 channels x 64 tiles (8 wavefronts, two tiles each along K), where registers allow.
-hipError_t launch_wino_fused(const WinoGeom& g, int config, const float* AT, const float* Ub, const float* Vb,
-                             const float* bias, float* y, hipStream_t s)
+namespace {
+
+hipError_t dispatch_fused(const WinoGeom& g, int config, const float* AT, const float* Ub, const float* Vb, const float* bias,
+                          float* y, hipStream_t s, const FusedRange& r)
 {
-    if (!AT || !Ub || !Vb || !y) return hipErrorInvalidValue;
-    if (g.blocked != 1 || g.kg * 16 < g.K || g.pg * 16 < g.P) return hipErrorInvalidValue;
-    if (!wino_fused_available(g.n, g.k)) return hipErrorInvalidValue;
-    if (config == 1 && !wino_fused_has_big_block(g.n, g.k)) return hipErrorInvalidValue;
 #define MNN_FUSED(NN, KK)                                                                       \
     if (g.n == NN && g.k == KK) {                                                                \
         if constexpr (fits_big(NN, KK)) {                                                        \
-            if (config == 1) return launch_fused_t<NN, KK, 2, 1, 2, 4, bkg_for(NN + KK - 1), kStages>(g, AT, Ub, Vb, bias, y, s);  \
+            if (config == 1) return launch_fused_t<NN, KK, 2, 1, 2, 4, bkg_for(NN + KK - 1), kStages>(g, AT, Ub, Vb, bias, y, s, r);  \
         }                                                                                        \
-        return launch_fused_t<NN, KK, 1, 1, 2, 2, bkg_for(NN + KK - 1), kStages>(g, AT, Ub, Vb, bias, y, s);                       \
+        return launch_fused_t<NN, KK, 1, 1, 2, 2, bkg_for(NN + KK - 1), kStages>(g, AT, Ub, Vb, bias, y, s, r);                       \
     }
     MNN_FUSED(2, 2) MNN_FUSED(3, 2) MNN_FUSED(4, 2) MNN_FUSED(5, 2) MNN_FUSED(6, 2) MNN_FUSED(7, 2)
     MNN_FUSED(2, 3) MNN_FUSED(3, 3) MNN_FUSED(4, 3) MNN_FUSED(5, 3) MNN_FUSED(6, 3)
@@ -336,6 +352,52 @@ hipError_t launch_wino_fused(const WinoGeom& g, int config, const float* AT, con
     MNN_FUSED(6, 4) MNN_FUSED(5, 5) MNN_FUSED(6, 5) MNN_FUSED(4, 6) MNN_FUSED(5, 6) MNN_FUSED(3, 7) MNN_FUSED(4, 7)
 #undef MNN_FUSED
     return hipErrorInvalidValue;
+}
+
+// workgroups of the 64 x 64 configuration the device holds at once, per (n, k); 0 = not asked yet
+std::mutex g_resident_mu;
+std::map<std::pair<int, int>, int> g_resident64;
+
+}  // namespace
+
+// config 0: 32 channels x 32 tiles per workgroup (4 wavefronts, one 16x16 tile each);
+// config 1: 64 channels x 64 tiles (8 wavefronts, two tiles each along K), where registers allow.
+//
+// The 64 x 64 workgroups are few and long (two per CU): a grid of 1.5 times what the device holds runs as two
+// rounds, the second half empty.  When the last round would be at most 60 % full, config 1 therefore covers only the
+// tile blocks that fill whole rounds and the rest of the tiles is launched as 32 x 32 workgroups, which are
+// short and pack five to a CU (same operands, same order of additions: the same bits).
+hipError_t launch_wino_fused(const WinoGeom& g, int config, const float* AT, const float* Ub, const float* Vb,
+                             const float* bias, float* y, hipStream_t s)
+{
+    if (!AT || !Ub || !Vb || !y) return hipErrorInvalidValue;
+    if (g.blocked != 1 || g.kg * 16 < g.K || g.pg * 16 < g.P) return hipErrorInvalidValue;
+    if (!wino_fused_available(g.n, g.k)) return hipErrorInvalidValue;
+    if (config == 1 && !wino_fused_has_big_block(g.n, g.k)) return hipErrorInvalidValue;
+    if (config != 1) return dispatch_fused(g, 0, AT, Ub, Vb, bias, y, s, FusedRange{});
+    int resident = 0;
+    {
+        std::lock_guard<std::mutex> lk(g_resident_mu);
+        int& slot = g_resident64[{g.n, g.k}];
+        if (slot == 0) {
+            FusedRange q;
+            q.resident = &slot;
+            const hipError_t e = dispatch_fused(g, 1, AT, Ub, Vb, bias, y, s, q);
+            if (e != hipSuccess) { slot = 0; return e; }
+        }
+        resident = slot;
+    }
+    const int kblocks = (g.K + 63) / 64, pblocks = (g.P + 63) / 64;
+    const long long total = (long long)kblocks * pblocks;
+    int p_big = pblocks;                                    // tile blocks of 64 the big configuration takes
+    if (resident > 0 && total > resident) {
+        const long long rounds = total / resident;
+        const long long last = total - rounds * resident;  // workgroups of the last, partial round
+        if (last > 0 && last * 10 <= (long long)resident * 6) p_big = (int)(rounds * resident / kblocks);
+    }
+    hipError_t e = dispatch_fused(g, 1, AT, Ub, Vb, bias, y, s, FusedRange{0, p_big, nullptr});
+    if (e != hipSuccess || p_big == pblocks) return e;
+    return dispatch_fused(g, 0, AT, Ub, Vb, bias, y, s, FusedRange{2 * p_big, -1, nullptr});
 }
 
 }  // namespace mnnconv
