@@ -93,7 +93,9 @@ struct mnn_chain_s {
             for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st)
                 if (im->has_stage(st))
                     k += (st == MNN_STAGE_GEMM && im->strassen) ? im->strassen->launches()
-                         : (st == MNN_STAGE_GEMM && im->gemm_splitk > 1) ? 2 : 1;                // + the slice reduction
+                         : (st == MNN_STAGE_GEMM && im->gemm_splitk > 1) ? 2                    // + the slice reduction
+                         : (st == MNN_STAGE_GEMM && im->scheme.kind == MNN_SCHEME_WINOGRAD && im->scheme.variant != MNN_WINO_UNFUSED)
+                               ? wino_fused_launch_count(im->wg, im->scheme.variant - 1) : 1;
         return k;
     }
 

@@ -60,11 +60,13 @@ hipError_t launch_output_transform_rect(const WinoGeom& g, const float* ATh, con
 
 // Winograd-domain product with the inverse transform and bias fused in:
 // y = A^T [ sum_c U (.) V ] A + bias, operands in the blocked layout.  M is never stored.
-// config 0: 32 channels x 32 tiles per workgroup; config 1: 64 x 32 (only where wino_fused_has_big_block).
+// config 0: 32 channels x 32 tiles per workgroup; config 1: 64 x 64 (only where wino_fused_has_big_block), with the
+// tiles of a mostly empty last round of workgroups handed to 32 x 32 workgroups (up to two launches).
 bool wino_fused_available(int n, int k);
 bool wino_fused_has_big_block(int n, int k);
 hipError_t launch_wino_fused(const WinoGeom& g, int config, const float* AT /*host*/, const float* Ub,
                              const float* Vb, const float* bias, float* y, hipStream_t s);
+int wino_fused_launch_count(const WinoGeom& g, int config);      // kernels one such call enqueues
 
 // Batched GEMM  D_b[m][col] = sum_r At_b[r][m] * B_b[r][col] (+ bias[m]).
 //   At: [batch][R][lda]  (A stored transposed, m contiguous; lda % 4 == 0, 16-byte aligned)

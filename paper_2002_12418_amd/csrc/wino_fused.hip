@@ -360,6 +360,37 @@ std::map<std::pair<int, int>, int> g_resident64;
 
 }  // namespace
 
+namespace {
+
+// How many tile blocks of 64 the 64 x 64 configuration takes (the rest goes to 32 x 32 workgroups): all of them, or
+// those that fill whole rounds of resident workgroups when the last round would be at most 60 % full.
+hipError_t big_block_share(const WinoGeom& g, int* p_big)
+{
+    int resident = 0;
+    {
+        std::lock_guard<std::mutex> lk(g_resident_mu);
+        int& slot = g_resident64[{g.n, g.k}];
+        if (slot == 0) {
+            FusedRange q;
+            q.resident = &slot;
+            const hipError_t e = dispatch_fused(g, 1, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, q);
+            if (e != hipSuccess) { slot = 0; return e; }
+        }
+        resident = slot;
+    }
+    const int kblocks = (g.K + 63) / 64, pblocks = (g.P + 63) / 64;
+    const long long total = (long long)kblocks * pblocks;
+    *p_big = pblocks;
+    if (resident > 0 && total > resident) {
+        const long long rounds = total / resident;
+        const long long last = total - rounds * resident;  // workgroups of the last, partial round
+        if (last > 0 && last * 10 <= (long long)resident * 6) *p_big = (int)(rounds * resident / kblocks);
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+
 // config 0: 32 channels x 32 tiles per workgroup (4 wavefronts, one 16x16 tile each);
 // config 1: 64 channels x 64 tiles (8 wavefronts, two tiles each along K), where registers allow.
 //
@@ -375,29 +406,23 @@ hipError_t launch_wino_fused(const WinoGeom& g, int config, const float* AT, con
     if (!wino_fused_available(g.n, g.k)) return hipErrorInvalidValue;
     if (config == 1 && !wino_fused_has_big_block(g.n, g.k)) return hipErrorInvalidValue;
     if (config != 1) return dispatch_fused(g, 0, AT, Ub, Vb, bias, y, s, FusedRange{});
-    int resident = 0;
-    {
-        std::lock_guard<std::mutex> lk(g_resident_mu);
-        int& slot = g_resident64[{g.n, g.k}];
-        if (slot == 0) {
-            FusedRange q;
-            q.resident = &slot;
-            const hipError_t e = dispatch_fused(g, 1, AT, Ub, Vb, bias, y, s, q);
-            if (e != hipSuccess) { slot = 0; return e; }
-        }
-        resident = slot;
-    }
-    const int kblocks = (g.K + 63) / 64, pblocks = (g.P + 63) / 64;
-    const long long total = (long long)kblocks * pblocks;
-    int p_big = pblocks;                                    // tile blocks of 64 the big configuration takes
-    if (resident > 0 && total > resident) {
-        const long long rounds = total / resident;
-        const long long last = total - rounds * resident;  // workgroups of the last, partial round
-        if (last > 0 && last * 10 <= (long long)resident * 6) p_big = (int)(rounds * resident / kblocks);
-    }
+    int p_big = 0;
+    const hipError_t eq = big_block_share(g, &p_big);
+    if (eq != hipSuccess) return eq;
+    const int pblocks = (g.P + 63) / 64;
     hipError_t e = dispatch_fused(g, 1, AT, Ub, Vb, bias, y, s, FusedRange{0, p_big, nullptr});
     if (e != hipSuccess || p_big == pblocks) return e;
     return dispatch_fused(g, 0, AT, Ub, Vb, bias, y, s, FusedRange{2 * p_big, -1, nullptr});
+}
+
+// kernels one call of launch_wino_fused enqueues (1, or 2 when the tail of the tiles goes to 32 x 32 workgroups)
+int wino_fused_launch_count(const WinoGeom& g, int config)
+{
+    if (config != 1 || !wino_fused_has_big_block(g.n, g.k)) return 1;
+    int p_big = 0;
+    if (big_block_share(g, &p_big) != hipSuccess) { (void)hipGetLastError(); return 1; }
+    const int pblocks = (g.P + 63) / 64;
+    return (p_big > 0 && p_big < pblocks) ? 2 : 1;
 }
 
 }  // namespace mnnconv
