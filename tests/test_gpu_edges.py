@@ -170,3 +170,24 @@ def test_degenerate_shapes_every_scheme(layer):
         got = y.cpu().numpy()
         assert got.shape == ref.shape and np.isfinite(got).all()
         assert oracle.error_ratio(got, ref) <= tol_for(chosen, layer.k_long, m), (layer.name, chosen.label(layer.k_long))
+
+
+def test_fused_64x64_with_a_tail_of_32x32_workgroups():
+    """50176 tiles and 64 output channels make 784 workgroups of 64 x 64, one and a half times what the device holds:
+    the library gives the 64 x 64 kernel the blocks of the full round and the rest of the tiles to 32 x 32 workgroups.
+    Whole tensor against the oracle, and the same bits as the 32 x 32 arrangement alone (same order of additions)."""
+    m = mnn()
+    layer = ConvLayer("split_tail", 16, 8, 112, 112, 64, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 870)
+    x, w, b = draw(layer)
+    ref = oracle.conv2d(x, w, b, stride=1, pad=1)
+    xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+    outs = {}
+    for variant in (m.WINO_FUSED_OUT_64, m.WINO_FUSED_OUT_32):
+        opt = m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=2, force_variant=variant)
+        with m.ConvPlan.for_layer(layer, options=opt) as plan:
+            y = torch.full(plan.out_shape, float("nan"), dtype=torch.float32, device="cuda")
+            plan.run(xd, wd, bd, y)
+            torch.cuda.synchronize()
+        assert oracle.error_ratio(y.cpu().numpy(), ref) <= 1e-4
+        outs[variant] = y
+    assert torch.equal(outs[m.WINO_FUSED_OUT_64], outs[m.WINO_FUSED_OUT_32])
