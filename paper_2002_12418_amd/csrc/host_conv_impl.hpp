@@ -127,6 +127,9 @@ struct Impl {
                     return fail(MNN_E_UNSUPPORTED, "Winograd-domain tensors too large");
                 if ((rc = alloc_zero(&U, U_bytes, "hipMalloc U"))) return rc;
                 if ((rc = alloc_transient(&V, V_bytes, "hipMalloc V"))) return rc;
+                // asks the runtime once how many 64 x 64 workgroups the device holds, here and not in the first launch
+                // (which may be recorded into a graph)
+                (void)wino_fused_launch_count(wg, s.variant - 1);
                 return MNN_OK;
             }
             if ((long long)wg.C * wg.ldp >= (1ll << 31) || (long long)wg.K * wg.ldp >= (1ll << 31))
