@@ -316,7 +316,7 @@ constexpr int bkg_for(int alpha) { return alpha <= 6 ? 4 : 2; }
 // instead of three (F(2,7) C = 64: 0.346 -> 0.320 ms, F(4,5) C = 128: 0.111 -> 0.103 ms).
 constexpr int kStages = 2;
 
-constexpr bool fits_big(int n, int k) { return (2 * (4 * (n + k - 1) + 4 * n * n)) <= 190; }
+constexpr bool fits_big(int n, int k) { return (2 * (4 * (n + k - 1) + 4 * n * n)) <= 192; }
 // one 16x16 tile per wavefront must leave room for two wavefronts per SIMD (256 registers each)
 constexpr bool fits_small(int n, int k) { return 4 * (n + k - 1) + 4 * n * n <= 230; }
 
