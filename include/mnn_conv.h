@@ -24,7 +24,11 @@
  *   - Streams are hipStream_t passed as void* (NULL = the default stream).
  *   - A plan owns its workspace; mnn_conv_run allocates nothing and never
  *     synchronises the host (preparation-execution decoupling, Section 3.2).
- *     One plan must not be used from two streams at the same time.
+ *   - Threading: plan, chain and Strassen handles are not thread-safe.  The calls that run a handle
+ *     (mnn_conv_run, _run_stage, _run_timed, _set_weights, mnn_chain_run / _replay, mnn_strassen_run) share its
+ *     workspace (V, M, the split-K slices), so one handle serves one stream at a time: work enqueued through it
+ *     on a second stream, or from a second thread, while earlier work is still running races on that workspace.
+ *     Different handles are independent; the process-wide caches are guarded by locks.
  */
 #ifndef MNN_CONV_H
 #define MNN_CONV_H
@@ -155,11 +159,13 @@ int mnn_conv_options_default(mnn_conv_options* opt);
 int mnn_conv_plan(const mnn_conv_shape* shape, const mnn_conv_geom* geom,
                   const mnn_conv_options* options, void* stream, mnn_conv_plan_t* out_plan);
 
-/* The scheme the plan runs.  Host. */
+/* The scheme the plan runs: the member of the scheme pool that the cost evaluation of Section 3.2 (1) selected
+ * (or the forced one), with the time it measured.  Host. */
 int mnn_conv_plan_scheme(mnn_conv_plan_t plan, mnn_scheme* out);
 
-/* All schemes the planner considered, timed ones carrying est_ms >= 0.  Writes at
- * most `cap` entries to out (may be NULL with cap 0) and the total to *count.  Host. */
+/* The scheme pool of Section 3.2 (1) for this layer -- all schemes the planner considered -- with the cost
+ * measured for each (est_ms >= 0; < 0: pruned, did not fit or does not apply).  Writes at most `cap` entries to
+ * out (may be NULL with cap 0) and the total to *count.  Host. */
 int mnn_conv_plan_candidates(mnn_conv_plan_t plan, mnn_scheme* out, int32_t cap, int32_t* count);
 
 /* Human-readable description of what the plan launches, e.g. "F(4,3) unfused gemm=128x64x16_w2x2".
@@ -169,7 +175,8 @@ int mnn_conv_plan_describe(mnn_conv_plan_t plan, char* buf, size_t cap);
 /* Geometry of the plan.  Host. */
 int mnn_conv_plan_info(mnn_conv_plan_t plan, mnn_plan_info* out);
 
-/* Bytes of device memory the plan owns (workspace + prepared weights). */
+/* Bytes of device memory the plan owns (workspace + prepared weights): what pre-inference allocated so that
+ * inference allocates nothing (preparation-execution decoupling, Section 3.2).  0 for a NULL plan. */
 size_t mnn_conv_workspace_bytes(mnn_conv_plan_t plan);
 
 /*
@@ -179,7 +186,9 @@ size_t mnn_conv_workspace_bytes(mnn_conv_plan_t plan);
  * weights (Winograd: U = G w G^T, Section 3.3.1) are rebuilt only when `weight`
  * differs from the pointer of the previous call or after
  * mnn_conv_invalidate_weights; otherwise the call launches only the
- * per-inference stages.  Returns MNN_E_HIP if a launch fails.
+ * per-inference stages.  The library cannot see the CONTENTS of `weight` change:
+ * after writing new values to the same address call mnn_conv_set_weights (or
+ * mnn_conv_invalidate_weights) before the next run.  Returns MNN_E_HIP if a launch fails.
  */
 int mnn_conv_run(mnn_conv_plan_t plan, const float* input, const float* weight,
                  const float* bias, float* output, void* stream);
@@ -197,7 +206,16 @@ int mnn_conv_run_timed(mnn_conv_plan_t plan, const float* input, const float* we
 int mnn_conv_run_stage(mnn_conv_plan_t plan, int32_t stage, const float* input, const float* weight,
                        const float* bias, float* output, void* stream);
 
-/* Forces the weight preparation to run again on the next mnn_conv_run. */
+/* Prepares the weights now: enqueues G w G^T (Section 3.3.1; computed once per weight set, not per inference)
+ * or the transposition of the 1x1 / sliding-window schemes on `stream` and remembers `weight` as prepared, so
+ * that the following mnn_conv_run calls with this pointer launch only the per-inference stages.  This is the
+ * explicit form of what mnn_conv_run does when it sees a new pointer; it is the call to make after the values
+ * behind an unchanged pointer were rewritten.  weight: device, float32, KCRS, read only.
+ * Errors: MNN_E_INVALID_ARG (NULL), MNN_E_HIP. */
+int mnn_conv_set_weights(mnn_conv_plan_t plan, const float* weight, void* stream);
+
+/* Marks the prepared weights (G w G^T of Section 3.3.1, computed once per weight set) as stale: the next
+ * mnn_conv_run prepares them again from its `weight` argument.  Host; launches nothing. */
 int mnn_conv_invalidate_weights(mnn_conv_plan_t plan);
 
 /* Device address and size in bytes of one of the plan's buffers (MNN_BUF_*);
@@ -208,6 +226,9 @@ int mnn_conv_plan_buffer(mnn_conv_plan_t plan, int32_t which, void** ptr, size_t
  * dst: host, at least `bytes` bytes; bytes must not exceed the buffer size. */
 int mnn_conv_read_buffer(mnn_conv_plan_t plan, int32_t which, void* dst, size_t bytes, void* stream);
 
+/* Ends what pre-inference set up (Section 3.2): frees the plan's workspace and prepared weights.  The choices it
+ * left in the process-wide cache stay.  The caller makes sure that no work enqueued through the plan is still
+ * running.  NULL is allowed. */
 void mnn_conv_plan_destroy(mnn_conv_plan_t plan);
 
 /*

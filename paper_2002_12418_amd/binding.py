@@ -100,6 +100,7 @@ def _load() -> ctypes.CDLL:
     L.mnn_conv_run_timed.argtypes = [vp, vp, vp, vp, vp, vp, c_int32, POINTER(c_float)]
     L.mnn_conv_run_stage.argtypes = [vp, c_int32, vp, vp, vp, vp, vp]
     L.mnn_conv_invalidate_weights.argtypes = [vp]
+    L.mnn_conv_set_weights.argtypes = [vp, vp, vp]
     L.mnn_conv_plan_buffer.argtypes = [vp, c_int32, POINTER(vp), POINTER(c_size_t)]
     L.mnn_conv_read_buffer.argtypes = [vp, c_int32, vp, c_size_t, vp]
     L.mnn_conv_plan_destroy.argtypes = [vp]
@@ -402,6 +403,7 @@ class ConvPlan:
         _check(lib.mnn_conv_plan_info(self._h, byref(info)))
         self.info = {f: int(getattr(info, f)) for f, _ in _Info._fields_}
         self.out_shape = (n, c_out, self.info["h_out"], self.info["w_out"])
+        self._w_seen = None          # (address, torch version counter) of the weight tensor last handed to the library
 
     @classmethod
     def for_layer(cls, layer, options: Optional[Options] = None, stream=None) -> "ConvPlan":
@@ -445,9 +447,29 @@ class ConvPlan:
         if y is None:
             y = torch.empty(self.out_shape, dtype=torch.float32, device=x.device)
         self._check_tensors(x, w, b, y)
+        self._note_weight(w)
         _check(lib.mnn_conv_run(self._h, x.data_ptr(), w.data_ptr(), b.data_ptr() if b is not None else None,
                                 y.data_ptr(), _stream_handle(stream)))
         return y
+
+    def _note_weight(self, w):
+        # The library re-prepares the weights when the pointer changes; it cannot see new values behind the same
+        # pointer (an in-place update, or a new tensor the allocator put at the old address).  torch counts in-place
+        # writes per tensor, and the tensor object is kept alive here so that its address cannot be reused.
+        seen = (w.data_ptr(), w._version, id(w))
+        if self._w_seen is not None and self._w_seen[0][0] == seen[0] and self._w_seen[0] != seen:
+            _check(lib.mnn_conv_invalidate_weights(self._h))
+        self._w_seen = (seen, w)
+
+    def set_weights(self, w, stream=None):
+        """mnn_conv_set_weights: prepare the weights now (after new values were written behind the same pointer by
+        something torch's version counter does not see, e.g. another library)."""
+        import torch
+        n, c_in, h, wd, c_out, kh, kw = self.shape
+        if tuple(w.shape) != (c_out, c_in, kh, kw) or w.dtype != torch.float32 or not w.is_contiguous() or not w.is_cuda:
+            raise ValueError("weight: expected contiguous float32 device tensor of shape (c_out, c_in, kh, kw)")
+        _check(lib.mnn_conv_set_weights(self._h, w.data_ptr(), _stream_handle(stream)))
+        self._w_seen = ((w.data_ptr(), w._version, id(w)), w)
 
     def run_stage(self, stage: int, x, w, b, y, stream=None):
         self._check_tensors(x, w, b, y)
@@ -482,6 +504,7 @@ class ConvPlan:
         if getattr(self, "_h", None) is not None and self._h.value:
             lib.mnn_conv_plan_destroy(self._h)
             self._h = c_void_p()
+        self._w_seen = None
 
     def __del__(self):
         try:

@@ -16,7 +16,7 @@ INCLUDE = os.path.join(os.path.dirname(PKG), "include")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(PKG, "libmnnconv.so")
 
-SOURCES = ["api.cpp", "transforms.hip", "transforms_rect.hip", "gemm.hip", "direct.hip", "wino_fused.hip", "gemm_bf16.hip", "strassen.hip", "microbench.hip"]
+SOURCES = ["api.cpp", "transforms.hip", "transforms_rect.hip", "gemm.hip", "weight_layout.hip", "fill.hip", "wino_fused.hip", "gemm_bf16.hip", "strassen.hip", "microbench.hip"]
 
 # -packed-fp32-ops is switched off: hand-checked scalar fp32 code only.
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I", INCLUDE, "-I", CSRC,
@@ -47,6 +47,10 @@ def _compile(src: str) -> str:
 def build_library(verbose: bool = True) -> str:
     """Compile every source for gfx950 and link paper_2002_12418_amd/libmnnconv.so."""
     os.makedirs(OBJ_DIR, exist_ok=True)
+    wanted = {os.path.splitext(src)[0] + ".o" for src in SOURCES}
+    for stale in os.listdir(OBJ_DIR):                      # objects of sources that were renamed or removed
+        if stale.endswith(".o") and stale not in wanted:
+            os.remove(os.path.join(OBJ_DIR, stale))
     with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = LIB_PATH + ".tmp"

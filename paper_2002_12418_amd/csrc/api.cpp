@@ -228,7 +228,7 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
             if (plan->cands.size() == 1) {
                 chosen = plan->cands[0];
             } else {
-                // scratch tensors for the timing launches (contents do not affect kernel time)
+                // scratch tensors for the timing launches
                 Scratch sc;
                 const size_t xb = (size_t)L.s.n * L.s.c_in * L.s.h * L.s.w * sizeof(float);
                 const size_t wb = (size_t)L.s.c_out * L.s.c_in * L.s.kh * L.s.kw * sizeof(float);
@@ -238,11 +238,16 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
                     delete plan;
                     return fail_hip(e, "hipMalloc planner scratch");
                 }
-                if ((e = hipMemset(sc.x, 0, xb)) != hipSuccess || (e = hipMemset(sc.w, 0, wb)) != hipSuccess) {
+                // seeded values with the spread of real activations and He-initialised weights: the time of the
+                // matrix-core stage depends on the operand bits (power, sustained clock), all-zero tensors flatter it
+                const float wr = std::sqrt(6.f / (float)(L.s.c_in * L.s.kh * L.s.kw));
+                if ((e = launch_fill_pattern(sc.x, xb / sizeof(float), 0x2002u, -1.f, 1.f, s)) != hipSuccess ||
+                    (e = launch_fill_pattern(sc.w, wb / sizeof(float), 0x12418u, -wr, wr, s)) != hipSuccess) {
                     delete plan;
-                    return fail_hip(e, "hipMemset planner scratch");
+                    return fail_hip(e, "planner scratch fill");
                 }
                 double best_pred = -1.0;
+                int last_skip = MNN_E_OOM;
                 for (const auto& c : plan->cands) {
                     const double pm = predict_ms(L, c);
                     if (best_pred < 0.0 || pm < best_pred) best_pred = pm;
@@ -250,11 +255,16 @@ int plan_impl(const mnn_conv_shape* shape, const mnn_conv_geom* geom, const mnn_
                 for (auto& c : plan->cands) {
                     if (o.prune_ratio > 1.f && predict_ms(L, c) > (double)o.prune_ratio * best_pred) { c.est_ms = -1.f; continue; }
                     rc = time_candidate(L, o, &c, sc, s);
-                    if (rc == MNN_E_OOM) { c.est_ms = -1.f; (void)hipGetLastError(); continue; }   // does not fit: not a candidate
+                    // a scheme that does not fit in memory or that the kernels do not cover for this shape is not a
+                    // candidate; the cheapest of those that apply is selected (Section 3.2 (1))
+                    if (rc == MNN_E_OOM || rc == MNN_E_UNSUPPORTED) { c.est_ms = -1.f; (void)hipGetLastError(); last_skip = rc; continue; }
                     if (rc) { delete plan; return rc; }
                 }
                 const int pick = select_scheme(plan->cands.data(), (int)plan->cands.size(), wino_k(L));
-                if (pick < 0) { delete plan; return fail(MNN_E_OOM, "no candidate scheme could be timed"); }
+                if (pick < 0) {
+                    delete plan;
+                    return fail(last_skip == MNN_E_UNSUPPORTED ? MNN_E_UNSUPPORTED : MNN_E_OOM, "no candidate scheme could be timed");
+                }
                 chosen = plan->cands[pick];
             }
             if (use_cache) {
@@ -405,6 +415,17 @@ int mnn_conv_run_timed(mnn_conv_plan_t plan, const float* input, const float* we
     plan->cached_weight = weight;
     plan->weights_valid = true;
     for (int st = 0; st < MNN_STAGE_COUNT; ++st) stage_ms[st] = (float)(acc[st] / iters);
+    return MNN_OK;
+}
+
+int mnn_conv_set_weights(mnn_conv_plan_t plan, const float* weight, void* stream)
+{
+    if (!plan) return fail(MNN_E_INVALID_ARG, "plan is NULL");
+    if (!weight) return fail(MNN_E_INVALID_ARG, "weight must not be NULL");
+    int rc = plan->impl.run_stage(MNN_STAGE_FILTER, nullptr, weight, nullptr, nullptr, (hipStream_t)stream);
+    if (rc) return rc;
+    plan->cached_weight = weight;
+    plan->weights_valid = true;
     return MNN_OK;
 }
 
@@ -631,8 +652,9 @@ int mnn_conv_calibrate(void* stream, mnn_device_model* out)
     mnn_device_model m{};
     do {
         if ((e = hipMalloc((void**)&a, (size_t)R * M * 4)) != hipSuccess || (e = hipMalloc((void**)&b, copy_bytes)) != hipSuccess ||
-            (e = hipMalloc((void**)&d, copy_bytes)) != hipSuccess || (e = hipMemset(a, 0, (size_t)R * M * 4)) != hipSuccess ||
-            (e = hipMemset(b, 0, copy_bytes)) != hipSuccess || (e = hipEventCreate(&e0)) != hipSuccess ||
+            (e = hipMalloc((void**)&d, copy_bytes)) != hipSuccess ||
+            (e = launch_fill_pattern(a, (size_t)R * M, 0x5bu, -0.5f, 0.5f, s)) != hipSuccess ||
+            (e = launch_fill_pattern(b, copy_bytes / sizeof(float), 0x5cu, -1.f, 1.f, s)) != hipSuccess || (e = hipEventCreate(&e0)) != hipSuccess ||
             (e = hipEventCreate(&e1)) != hipSuccess) {
             rc = fail_hip(e, "calibration set-up");
             break;

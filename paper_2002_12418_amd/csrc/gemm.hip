@@ -23,6 +23,7 @@
 // then hit the same L2.
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
+#include "xcd_remap.hpp"
 #include "gemm_epilogue.hpp"
 
 namespace mnnconv {
@@ -30,15 +31,6 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
-
-constexpr int kXcds = 8;
-
-__device__ __forceinline__ int xcd_remap(int bid, int total)
-{
-    const int per = total / kXcds, rem = total % kXcds;
-    const int xcd = bid % kXcds, loc = bid / kXcds;
-    return xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
-}
 
 // MODE 0: B read element by element through the (col / L, col % L) mapping; 1: the same with 16-byte
 // loads; 2: B gathered from an NCHW tensor (implicit GEMM of the sliding-window convolution).
@@ -90,7 +82,7 @@ __global__ __launch_bounds__(WM * WN * WK * 64) void gemm_f32_kernel(GemmProblem
     const int wm = wmn % WM, wn = wmn / WM;
 
     const int splitk = p.splitk > 1 ? p.splitk : 1;
-    const int wg = xcd_remap((int)blockIdx.x, total * splitk);
+    const int wg = (int)xcd_contiguous(blockIdx.x, (unsigned)(total * splitk));
     const int logical = wg / splitk;          // slices of one tile are neighbours: same XCD, same L2
     const int split = wg % splitk;
     const int tm = logical % tilesM;

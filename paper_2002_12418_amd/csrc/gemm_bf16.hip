@@ -21,6 +21,7 @@
 // 8*(l/32) .. +7, column l%32) is four dwords, row pairs 4*(l/32) .. +3.
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
+#include "xcd_remap.hpp"
 #include "gemm_epilogue.hpp"
 
 namespace mnnconv {
@@ -29,15 +30,6 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-
-constexpr int kXcds = 8;
-
-__device__ __forceinline__ int xcd_remap(int bid, int total)
-{
-    const int per = total / kXcds, rem = total % kXcds;
-    const int xcd = bid % kXcds, loc = bid / kXcds;
-    return xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
-}
 
 // round-to-nearest-even bf16 of x, as the upper 16 bits of a float pattern (inputs are finite)
 __device__ __forceinline__ unsigned bf16_bits(float x)
@@ -86,7 +78,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmProblem p, 
     const int wm = wave % WM, wn = wave / WM;
 
     const int splitk = p.splitk > 1 ? p.splitk : 1;
-    const int wg = xcd_remap((int)blockIdx.x, total * splitk);
+    const int wg = (int)xcd_contiguous(blockIdx.x, (unsigned)(total * splitk));
     const int logical = wg / splitk;          // slices of one tile are neighbours: same XCD, same L2
     const int split = wg % splitk;
     const int tm = logical % tilesM;

@@ -23,6 +23,9 @@ struct Impl {
     // V, M and the split-K partials hold nothing between two runs.  A plan on its own allocates them;
     // a chain of layers binds them to a region of its arena instead (bind_transient).
     bool transient_external = false;
+    // The prepared weights live as long as the plan and are the plan's own allocation, except for the single-shot
+    // entry point that may not allocate: there U, too, is bound to a region of the caller-independent scratch array.
+    bool persistent_external = false;
 
     ~Impl() { release(); }
     Impl() = default;
@@ -31,7 +34,7 @@ struct Impl {
 
     void release()
     {
-        if (U) (void)hipFree(U);
+        if (U && !persistent_external) (void)hipFree(U);
         if (!transient_external) {
             if (V) (void)hipFree(V);
             if (M) (void)hipFree(M);
@@ -60,7 +63,21 @@ struct Impl {
         return alloc_zero(p, bytes, what);
     }
 
+    int alloc_persistent(float** p, size_t bytes, const char* what)
+    {
+        if (persistent_external) { *p = nullptr; return MNN_OK; }
+        return alloc_zero(p, bytes, what);
+    }
+
     static size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+    // everything bound from outside (persistent_external): U first, then the transient buffers
+    size_t external_bytes() const { return align256(U_bytes) + transient_bytes(); }
+    void bind_external(char* base)
+    {
+        U = reinterpret_cast<float*>(base);
+        bind_transient(base + align256(U_bytes));
+    }
+
     size_t transient_bytes() const { return align256(V_bytes) + align256(M_bytes) + align256(sk_partial_bytes); }
     void bind_transient(char* base)
     {
@@ -69,11 +86,13 @@ struct Impl {
         sk_partial = sk_partial_bytes ? reinterpret_cast<float*>(base + align256(V_bytes) + align256(M_bytes)) : nullptr;
     }
 
-    int prepare(const Layer& layer, const mnn_scheme& s, const mnn_conv_options& o, bool external_transient = false)
+    int prepare(const Layer& layer, const mnn_scheme& s, const mnn_conv_options& o, bool external_transient = false,
+                bool external_persistent = false)
     {
         L = layer;
         scheme = s;
         transient_external = external_transient;
+        persistent_external = external_persistent;
         const mnn_conv_shape& sh = L.s;
         ldk = round_up(sh.c_out, 4);
         if (s.prec != MNN_GEMM_FP32 && s.kind == MNN_SCHEME_WINOGRAD && s.variant != MNN_WINO_UNFUSED)
@@ -125,7 +144,7 @@ struct Impl {
                 V_bytes = (size_t)wg.cchunks * a2 * wg.pg * 64 * sizeof(float);
                 if (V_bytes >= ((size_t)1 << 40) || U_bytes >= ((size_t)1 << 40))
                     return fail(MNN_E_UNSUPPORTED, "Winograd-domain tensors too large");
-                if ((rc = alloc_zero(&U, U_bytes, "hipMalloc U"))) return rc;
+                if ((rc = alloc_persistent(&U, U_bytes, "hipMalloc U"))) return rc;
                 if ((rc = alloc_transient(&V, V_bytes, "hipMalloc V"))) return rc;
                 // asks the runtime once how many 64 x 64 workgroups the device holds, here and not in the first launch
                 // (which may be recorded into a graph)
@@ -137,7 +156,7 @@ struct Impl {
             U_bytes = a2 * sh.c_in * ldk * sizeof(float);
             V_bytes = a2 * sh.c_in * wg.ldp * sizeof(float);
             M_bytes = a2 * sh.c_out * wg.ldp * sizeof(float);
-            if ((rc = alloc_zero(&U, U_bytes, "hipMalloc U"))) return rc;
+            if ((rc = alloc_persistent(&U, U_bytes, "hipMalloc U"))) return rc;
             if ((rc = alloc_transient(&V, V_bytes, "hipMalloc V"))) return rc;
             if ((rc = alloc_transient(&M, M_bytes, "hipMalloc M"))) return rc;
             return MNN_OK;
@@ -146,14 +165,14 @@ struct Impl {
             if (!is_pointwise(L)) return fail(MNN_E_UNSUPPORTED, "GEMM scheme needs a 1x1 kernel, stride 1, no padding");
             if ((long long)sh.n * sh.h * sh.w >= (1ll << 31)) return fail(MNN_E_UNSUPPORTED, "too many pixels");
             U_bytes = (size_t)sh.c_in * ldk * sizeof(float);
-            return alloc_zero(&U, U_bytes, "hipMalloc Wt");
+            return alloc_persistent(&U, U_bytes, "hipMalloc Wt");
         }
         if (s.kind == MNN_SCHEME_DIRECT) {
             // implicit GEMM on the matrix cores: weights transposed to [C*kh*kw][ldk]
             if ((long long)sh.n * L.Ho * L.Wo >= (1ll << 31) || (long long)sh.n * sh.c_in * sh.h * sh.w >= (1ll << 31))
                 return fail(MNN_E_UNSUPPORTED, "tensor too large for the sliding-window kernel");
             U_bytes = (size_t)sh.c_in * sh.kh * sh.kw * ldk * sizeof(float);
-            int rcd = alloc_zero(&U, U_bytes, "hipMalloc Wt");
+            int rcd = alloc_persistent(&U, U_bytes, "hipMalloc Wt");
             if (rcd) return rcd;
             return MNN_OK;
         }
@@ -237,7 +256,18 @@ struct Impl {
                 if (!cached_gemm_choice(p, &c)) c = GemmChoice{0, 1};
                 return adopt(p, c);
             }
+            if (cached_gemm_choice(p, &c)) return adopt(p, c);
+            // the tile configurations are timed on operands with the spread of real U and V, not on the zeros the
+            // buffers hold after allocation (matrix-core power, and with it the clock, depends on the operand bits);
+            // afterwards the buffers, padding included, are zero again
+            hipError_t e;
+            if ((e = launch_fill_pattern(U, U_bytes / sizeof(float), 0x55u, -0.5f, 0.5f, s)) != hipSuccess ||
+                (e = launch_fill_pattern(V, V_bytes / sizeof(float), 0x56u, -2.f, 2.f, s)) != hipSuccess)
+                return fail_hip(e, "tuning operand fill");
             int rc = tune_gemm(p, s, &c);
+            if ((e = hipMemsetAsync(U, 0, U_bytes, s)) != hipSuccess || (e = hipMemsetAsync(V, 0, V_bytes, s)) != hipSuccess ||
+                (e = hipStreamSynchronize(s)) != hipSuccess)
+                return fail_hip(e, "tuning operand reset");
             return rc ? rc : adopt(p, c);
         }
         if (scheme.kind == MNN_SCHEME_GEMM1X1 && scheme.variant > 0) {
@@ -263,8 +293,9 @@ struct Impl {
             if ((e = hipMalloc((void**)&tx, xb)) != hipSuccess || (e = hipMalloc((void**)&ty, yb)) != hipSuccess ||
                 (e = hipMalloc((void**)&tb, (size_t)sh.c_out * sizeof(float))) != hipSuccess)
                 rc = fail_hip(e, "hipMalloc tuning scratch");
-            if (!rc && ((e = hipMemset(tx, 0, xb)) != hipSuccess || (e = hipMemset(tb, 0, (size_t)sh.c_out * sizeof(float))) != hipSuccess))
-                rc = fail_hip(e, "hipMemset tuning scratch");
+            if (!rc && ((e = launch_fill_pattern(tx, xb / sizeof(float), 0x57u, -1.f, 1.f, s)) != hipSuccess ||
+                        (e = launch_fill_pattern(tb, (size_t)sh.c_out, 0x58u, -0.1f, 0.1f, s)) != hipSuccess))
+                rc = fail_hip(e, "tuning scratch fill");
             GemmProblem p = scheme.kind == MNN_SCHEME_DIRECT ? direct_gemm_problem(tx, tb, ty) : pointwise_gemm_problem(tx, tb, ty);
             if (!rc) rc = tune_gemm(p, s, &c);
             if (tx) (void)hipFree(tx);
@@ -330,6 +361,11 @@ struct Impl {
                 e = launch_weight_transpose(w, U, sh.c_out, sh.c_in * sh.kh * sh.kw, ldk, s);
             else
                 e = launch_gemm_f32(direct_gemm_problem(x, b, y), s);
+        }
+        if (e == hipErrorInvalidValue) {
+            // a launcher's own check of what its kernel assumes (sizes, alignment, grid limits) said no
+            (void)hipGetLastError();
+            return fail(MNN_E_UNSUPPORTED, "stage %d of this scheme does not cover the layer's shape", st);
         }
         if (e != hipSuccess) return fail_hip(e, "kernel launch");
         return MNN_OK;

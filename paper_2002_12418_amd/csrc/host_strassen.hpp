@@ -78,8 +78,9 @@ struct Strassen {
             float *ta = nullptr, *tb = nullptr, *td = nullptr;
             int rc = MNN_OK;
             if ((e = hipMalloc((void**)&ta, ab)) != hipSuccess || (e = hipMalloc((void**)&tb, bb)) != hipSuccess ||
-                (e = hipMalloc((void**)&td, db)) != hipSuccess || (e = hipMemset(ta, 0, ab)) != hipSuccess ||
-                (e = hipMemset(tb, 0, bb)) != hipSuccess)
+                (e = hipMalloc((void**)&td, db)) != hipSuccess ||
+                (e = launch_fill_pattern(ta, ab / sizeof(float), 0x59u, -0.5f, 0.5f, s)) != hipSuccess ||
+                (e = launch_fill_pattern(tb, bb / sizeof(float), 0x5au, -1.f, 1.f, s)) != hipSuccess)
                 rc = fail_hip(e, "Strassen tuning scratch");
             if (!rc) {
                 GemmProblem p = top;
@@ -103,6 +104,10 @@ struct Strassen {
             // tile configuration of the one batched GEMM at the bottom, by timing like any other shape
             GemmProblem p = leaf_problem();
             p.variant = 0; p.splitk = 1; p.splitk_partial = nullptr;
+            const size_t nb = (size_t)pow7(levels);
+            if ((e = launch_fill_pattern(Ax[levels], nb * Rl(levels) * Ml(levels), 0x5du, -0.5f, 0.5f, s)) != hipSuccess ||
+                (e = launch_fill_pattern(Bx[levels], nb * Rl(levels) * Nl(levels), 0x5eu, -1.f, 1.f, s)) != hipSuccess)
+                return fail_hip(e, "Strassen tuning operand fill");
             int rc = tune_gemm(p, s, &choice);
             if (rc) return rc;
             if (choice.splitk > 1) {

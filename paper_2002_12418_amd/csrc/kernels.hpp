@@ -2,6 +2,7 @@
 // every launcher validates what its kernel assumes and returns hipError_t.
 #pragma once
 #include <hip/hip_runtime_api.h>
+#include <cstddef>
 #include <cstdint>
 
 namespace mnnconv {
@@ -128,6 +129,11 @@ hipError_t launch_strassen_combine(const StrassenView& v, const float* src, int 
 
 // Wt[r][k] = w[k][r], r < R = C*kh*kw, row length ldk (zero padded)
 hipError_t launch_weight_transpose(const float* w, float* Wt, int K, int R, int ldk, hipStream_t s);
+
+// Seeded pseudo-random floats in [lo, hi] (scratch tensors of the timing planner) and zeros written by a kernel
+// (dst 16-byte aligned), for memory that code under graph capture has to clear.
+hipError_t launch_fill_pattern(float* dst, size_t n_floats, unsigned seed, float lo, float hi, hipStream_t s);
+hipError_t launch_fill_zero(float* dst, size_t n_floats, hipStream_t s);
 
 // Device-rate probes: `workgroups` x 4 waves each issuing 4*iters fp32 32x32x2 matrix-core instructions
 // (out: workgroups*256 floats), and a 16-byte-per-lane copy of n_floats (multiple of 4, 16-byte aligned).

@@ -9,6 +9,7 @@
 // every multiply is a v_fma with a scalar operand.
 #include <hip/hip_runtime.h>
 #include "kernels.hpp"
+#include "xcd_remap.hpp"
 
 namespace mnnconv {
 
@@ -66,22 +67,13 @@ __global__ __launch_bounds__(256) void filter_transform_kernel(WinoGeom g, Filte
 struct __attribute__((packed, aligned(4))) Unaligned4 { float x, y, z, w; };
 struct __attribute__((packed, aligned(4))) Unaligned2 { float x, y; };
 
-// Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with an L2 of its own.  The remap gives every XCD
-// a contiguous range of the work instead, so that neighbouring workgroups -- which read overlapping tile halos and
-// the same image rows -- find them in the same L2.
-__device__ __forceinline__ long long xcd_contiguous(unsigned bid, unsigned total)
-{
-    const unsigned per = total / 8, rem = total % 8, xcd = bid % 8, loc = bid / 8;
-    return xcd < rem ? (long long)xcd * (per + 1) + loc : (long long)rem * (per + 1) + (long long)(xcd - rem) * per + loc;
-}
-
 // ---------------------------------------------------------------- input: V = B^T d B
 template <int A, bool BLOCKED>
 __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg<A, A> bt,
                                                               const float* __restrict__ x,
                                                               float* __restrict__ V)
 {
-    const long long idx = xcd_contiguous(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
+    const long long idx = (long long)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
     int c, p;
     if constexpr (BLOCKED) {
         // a wavefront owns 16 consecutive tiles x 4 consecutive channels = one 64-float block per position

@@ -32,6 +32,7 @@
 #include <mutex>
 #include <utility>
 #include "kernels.hpp"
+#include "xcd_remap.hpp"
 
 namespace mnnconv {
 namespace {
@@ -86,10 +87,9 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void wino_fused_kernel(WinoGeom g,
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WM, wn = wave / WM;
-    // Consecutive workgroup ids go round-robin to the 8 XCDs (one L2 each): give every XCD a contiguous range of the
-    // grid, so that the K blocks of one tile block (K blocks fastest) read their common V block through one L2.
-    const unsigned per = gridDim.x / 8, rem = gridDim.x % 8, xcd = blockIdx.x % 8, loc = blockIdx.x / 8;
-    const int wg = (int)(xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc);
+    // every XCD gets a contiguous range of the grid, so that the K blocks of one tile block (K blocks fastest)
+    // read their common V block through one L2
+    const int wg = (int)xcd_contiguous(blockIdx.x, gridDim.x);
     const int kb = wg % kblocks;
     const int pb = pb0 + wg / kblocks;         // pb0: first tile block of this launch (a launch may cover a range)
 

@@ -191,3 +191,31 @@ def test_fused_64x64_with_a_tail_of_32x32_workgroups():
         assert oracle.error_ratio(y.cpu().numpy(), ref) <= 1e-4
         outs[variant] = y
     assert torch.equal(outs[m.WINO_FUSED_OUT_64], outs[m.WINO_FUSED_OUT_32])
+
+
+def test_weights_rewritten_behind_the_same_pointer_are_prepared_again():
+    """The prepared weights (G w G^T, the transposed weights of the other schemes) are cached per weight pointer.
+    New values behind an unchanged pointer -- an in-place update, a rewrite torch does not count -- must not be served
+    from the old preparation: the binding notices torch's version counter, mnn_conv_set_weights is the explicit call."""
+    m = mnn()
+    layer = ConvLayer("rewrite", 2, 12, 14, 13, 10, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 830)
+    x, w, b = draw(layer)
+    rng = np.random.Generator(np.random.PCG64(BASE_SEED + 831))
+    w2 = rng.normal(0.0, 0.2, w.shape).astype(np.float32)
+    w3 = rng.normal(0.0, 0.2, w.shape).astype(np.float32)
+    refs = [oracle.conv2d(x, ww, b, pad=1) for ww in (w, w2, w3)]
+    xd, bd = torch.from_numpy(x).cuda(), torch.from_numpy(b).cuda()
+    for s, opt in all_forced(m, layer):
+        print(f"[case] rewrite {s.label(3)}", flush=True)
+        wd = torch.from_numpy(w).cuda()
+        with m.ConvPlan.for_layer(layer, options=opt) as plan:
+            y = plan.run(xd, wd, bd)
+            assert oracle.error_ratio(y.cpu().numpy(), refs[0]) <= tol_for(s, 3, m)
+            wd.copy_(torch.from_numpy(w2))                      # in place: same address, torch's counter moves
+            y = plan.run(xd, wd, bd)
+            assert oracle.error_ratio(y.cpu().numpy(), refs[1]) <= tol_for(s, 3, m), "stale prepared weights were used"
+            # a write that torch's counter of this tensor does not see (.data has a counter of its own), then the explicit call
+            wd.data.copy_(torch.from_numpy(w3))
+            plan.set_weights(wd)
+            y = plan.run(xd, wd, bd)
+            assert oracle.error_ratio(y.cpu().numpy(), refs[2]) <= tol_for(s, 3, m)

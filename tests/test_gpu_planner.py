@@ -72,15 +72,21 @@ def test_forced_scheme_and_weight_refresh():
         y = plan.run(xd, w2d, bd)
         torch.cuda.synchronize()
         assert oracle.error_ratio(y.cpu().numpy(), ref2) < 1e-4
-        # same pointer, new contents: stale until invalidated
-        w2d.copy_(wd)
-        y = plan.run(xd, w2d, bd)
+        # same pointer, new contents.  The C ABI itself keys the prepared weights on the pointer (raw call: stale) ...
+        w2d.data.copy_(wd)                                  # a write the binding's version check does not see
+        m.lib.mnn_conv_run(plan._h, xd.data_ptr(), w2d.data_ptr(), bd.data_ptr(), y.data_ptr(), 0)
         torch.cuda.synchronize()
         assert oracle.error_ratio(y.cpu().numpy(), ref2) < 1e-4
+        # ... until the caller says so
         plan.invalidate_weights()
         y = plan.run(xd, w2d, bd)
         torch.cuda.synchronize()
         assert oracle.error_ratio(y.cpu().numpy(), ref1) < 1e-4
+        # the binding notices an in-place write that torch counts, and prepares the weights again by itself
+        w2d.copy_(torch.from_numpy(w2).cuda())
+        y = plan.run(xd, w2d, bd)
+        torch.cuda.synchronize()
+        assert oracle.error_ratio(y.cpu().numpy(), ref2) < 1e-4
 
 
 def test_inadmissible_forced_schemes_are_refused():

@@ -1,9 +1,8 @@
 """Strassen's algorithm for the large matrix multiplication (Section 3.3.2) on the device.
 
 It reaches the plain product exactly up to rounding order, so the oracle is the definition: a float64 matrix
-product (numpy) of the float32 operands.  Tolerance: every level adds a few fp32 roundings per element on
-operands whose magnitude grows by at most 2x (sums of two or three quadrants), so L levels stay within
-(1 + 4 L) times the 1e-4 bound of the plain fp32 GEMM relative to max|D|; measured errors are about 1e-6.
+product (numpy) of the float32 operands.  Tolerance: the 1e-4 of max|D| that the plain fp32 GEMM is held to,
+whatever the number of levels (every level adds a few fp32 roundings per element; measured errors are about 1e-6).
 """
 import numpy as np
 import pytest
@@ -45,8 +44,8 @@ def test_strassen_against_float64_product(M, R, N, levels):
     assert np.isfinite(got).all()
     err = oracle.error_ratio(got, ref)
     print(f"[strassen] {M}x{R}x{N} levels={levels} err={err:.2e}", flush=True)
-    assert err <= 1e-4 * (1 + 4 * levels)
-    assert oracle.error_ratio(D2.cpu().numpy(), At.astype(np.float64).T @ B2.astype(np.float64)) <= 1e-4 * (1 + 4 * levels)
+    assert err <= 1e-4
+    assert oracle.error_ratio(D2.cpu().numpy(), At.astype(np.float64).T @ B2.astype(np.float64)) <= 1e-4
 
 
 def test_strassen_rejects_what_it_cannot_split():
@@ -78,7 +77,7 @@ def test_pointwise_convolution_through_strassen(levels):
         plan.run(xd, wd, bd, y)
         torch.cuda.synchronize()
     err = oracle.error_ratio(y.cpu().numpy(), ref)
-    assert err <= 1e-4 * (1 + 4 * levels), err
+    assert err <= 1e-4, err
 
 
 def test_planner_times_strassen_like_any_other_candidate():
@@ -95,7 +94,7 @@ def test_planner_times_strassen_like_any_other_candidate():
         assert [c.est_ms for c in cands if c.variant == chosen.variant][0] <= best * 1.02 * (1 + 1e-6)
         y = plan.run(*(torch.from_numpy(a).cuda() for a in (x, w, b)))
         torch.cuda.synchronize()
-    assert oracle.error_ratio(y.cpu().numpy(), oracle.conv2d(x, w, b)) <= 1e-4 * (1 + 4 * chosen.variant)
+    assert oracle.error_ratio(y.cpu().numpy(), oracle.conv2d(x, w, b)) <= 1e-4
     m.cache_clear()
 
 
@@ -113,4 +112,4 @@ def test_strassen_at_the_size_of_the_last_pointwise_layer(levels):
         sg.set_left(torch.from_numpy(At).cuda())
         sg.run(torch.from_numpy(B).cuda(), D)
         torch.cuda.synchronize()
-    assert oracle.error_ratio(D.cpu().numpy(), ref) <= 1e-4 * (1 + 4 * levels)
+    assert oracle.error_ratio(D.cpu().numpy(), ref) <= 1e-4
