@@ -193,6 +193,27 @@ size_t mnn_conv_workspace_bytes(mnn_conv_plan_t plan);
 int mnn_conv_run(mnn_conv_plan_t plan, const float* input, const float* weight,
                  const float* bias, float* output, void* stream);
 
+/*
+ * mnn_conv_run for callers that cannot allocate device memory at all: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  One call does what mnn_conv_plan with a forced fp32 scheme followed by
+ * mnn_conv_run does -- tile_n >= 2: Winograd F(tile_n, k) with separate transform and GEMM kernels (square
+ * kernels and kernels that are not square alike); tile_n == 0: the sliding window, or the 1x1 GEMM for a
+ * pointwise layer -- but the prepared weights, V and M live in a fixed array inside the library's code object
+ * (mnn_conv_static_scratch_bytes() = 64 MiB per GPU, held until the process ends) instead of a plan's workspace.
+ * The call allocates and frees no device memory, synchronises nothing, times nothing (the GEMM tile configuration
+ * comes from the shape alone) and prepares the weights on every call.  It enqueues one clearing kernel and the
+ * scheme's 2 to 4 kernels on `stream`.
+ * shape, geom: host.  input, weight, bias (may be NULL), output: device, float32, layouts above.
+ * Errors: MNN_E_INVALID_ARG; MNN_E_UNSUPPORTED when the scheme does not apply to the layer or its scratch
+ * memory (prepared weights + V + M, each rounded up to 256 bytes) exceeds the array -- the message names both
+ * sizes; MNN_E_HIP.
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap in time (different streams,
+ * different threads) race.  Calls on one stream are ordered and safe.
+ */
+int mnn_conv_run_static(const mnn_conv_shape* shape, const mnn_conv_geom* geom, int32_t tile_n, const float* input,
+                        const float* weight, const float* bias, float* output, void* stream);
+size_t mnn_conv_static_scratch_bytes(void);
+
 /* Same work as mnn_conv_run repeated `iters` times with HIP events around each
  * stage; synchronises `stream` and writes the mean milliseconds per stage to
  * stage_ms[MNN_STAGE_COUNT] (host; stages the scheme does not have get 0;

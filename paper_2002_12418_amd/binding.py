@@ -101,6 +101,9 @@ def _load() -> ctypes.CDLL:
     L.mnn_conv_run_stage.argtypes = [vp, c_int32, vp, vp, vp, vp, vp]
     L.mnn_conv_invalidate_weights.argtypes = [vp]
     L.mnn_conv_set_weights.argtypes = [vp, vp, vp]
+    L.mnn_conv_run_static.argtypes = [POINTER(_Shape), POINTER(_Geom), c_int32, vp, vp, vp, vp, vp]
+    L.mnn_conv_static_scratch_bytes.argtypes = []
+    L.mnn_conv_static_scratch_bytes.restype = c_size_t
     L.mnn_conv_plan_buffer.argtypes = [vp, c_int32, POINTER(vp), POINTER(c_size_t)]
     L.mnn_conv_read_buffer.argtypes = [vp, c_int32, vp, c_size_t, vp]
     L.mnn_conv_plan_destroy.argtypes = [vp]
@@ -517,6 +520,18 @@ class ConvPlan:
 
     def __exit__(self, *exc):
         self.close()
+
+
+def static_scratch_bytes() -> int:
+    return int(lib.mnn_conv_static_scratch_bytes())
+
+
+def conv_run_static(layer, tile_n: int, x, w, b, y, stream=None):
+    """mnn_conv_run_static: one convolution with no device allocation (scratch in the library's fixed array)."""
+    s, g = _shape_geom(layer.n, layer.c_in, layer.h, layer.w, layer.c_out, layer.kh, layer.kw, layer.stride, layer.pad, layer.dil)
+    _check(lib.mnn_conv_run_static(byref(s), byref(g), tile_n, x.data_ptr(), w.data_ptr(),
+                                   b.data_ptr() if b is not None else None, y.data_ptr(), _stream_handle(stream)))
+    return y
 
 
 def arena_plan(sizes: Sequence[int], first: Sequence[int], last: Sequence[int], align: int = 256):

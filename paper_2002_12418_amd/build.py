@@ -16,7 +16,7 @@ INCLUDE = os.path.join(os.path.dirname(PKG), "include")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(PKG, "libmnnconv.so")
 
-SOURCES = ["api.cpp", "transforms.hip", "transforms_rect.hip", "gemm.hip", "weight_layout.hip", "fill.hip", "wino_fused.hip", "gemm_bf16.hip", "strassen.hip", "microbench.hip"]
+SOURCES = ["api.cpp", "transforms.hip", "transforms_rect.hip", "gemm.hip", "weight_layout.hip", "fill.hip", "static_scratch.hip", "wino_fused.hip", "gemm_bf16.hip", "strassen.hip", "microbench.hip"]
 
 # -packed-fp32-ops is switched off: hand-checked scalar fp32 code only.
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I", INCLUDE, "-I", CSRC,

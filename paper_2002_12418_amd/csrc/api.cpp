@@ -368,6 +368,45 @@ int mnn_conv_run(mnn_conv_plan_t plan, const float* input, const float* weight, 
     return MNN_OK;
 }
 
+size_t mnn_conv_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int mnn_conv_run_static(const mnn_conv_shape* shape, const mnn_conv_geom* geom, int32_t tile_n, const float* input,
+                        const float* weight, const float* bias, float* output, void* stream)
+{
+    if (!input || !weight || !output) return fail(MNN_E_INVALID_ARG, "input, weight and output must not be NULL");
+    Layer L;
+    int rc = validate(shape, geom, &L);
+    if (rc) return rc;
+    if (tile_n < 0) return fail(MNN_E_INVALID_ARG, "tile_n must be 0 (no Winograd) or the n of F(n,k)");
+    mnn_conv_options o;
+    default_options(&o);
+    o.alpha_max = kMaxAlphaT;
+    const mnn_scheme sc = tile_n > 0 ? make_scheme(MNN_SCHEME_WINOGRAD, tile_n, MNN_GEMM_FP32, MNN_WINO_UNFUSED)
+                                     : make_scheme(is_pointwise(L) ? MNN_SCHEME_GEMM1X1 : MNN_SCHEME_DIRECT, 0, MNN_GEMM_FP32);
+    try {
+        Impl im;                                   // host object only: every device buffer is bound below
+        if ((rc = im.prepare(L, sc, o, /*external_transient=*/true, /*external_persistent=*/true))) return rc;
+        const size_t need = im.external_bytes();
+        if (need > kStaticScratchBytes)
+            return fail(MNN_E_UNSUPPORTED, "this layer needs %zu bytes of scratch memory, the static buffer holds %zu: plan it with "
+                        "mnn_conv_plan instead", need, (size_t)kStaticScratchBytes);
+        float* base = nullptr;
+        hipError_t e = static_scratch(&base);
+        if (e != hipSuccess) return fail_hip(e, "static scratch buffer");
+        im.bind_external(reinterpret_cast<char*>(base));
+        hipStream_t s = (hipStream_t)stream;
+        // the buffer keeps the last call's contents: the padding of the prepared weights and of V must read as zero
+        // (by a kernel, not a memset: the call may be recorded into a graph)
+        if ((e = launch_fill_zero(base, (Impl::align256(im.U_bytes) + Impl::align256(im.V_bytes)) / sizeof(float), s)) != hipSuccess)
+            return fail_hip(e, "scratch clear");
+        for (int st = MNN_STAGE_FILTER; st < MNN_STAGE_COUNT; ++st)
+            if ((rc = im.run_stage(st, input, weight, bias, output, s))) return rc;
+        return MNN_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(MNN_E_OOM, "host allocation failed");
+    }
+}
+
 int mnn_conv_run_stage(mnn_conv_plan_t plan, int32_t stage, const float* input, const float* weight,
                        const float* bias, float* output, void* stream)
 {

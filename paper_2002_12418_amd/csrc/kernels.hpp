@@ -135,6 +135,12 @@ hipError_t launch_weight_transpose(const float* w, float* Wt, int K, int R, int 
 hipError_t launch_fill_pattern(float* dst, size_t n_floats, unsigned seed, float lo, float hi, hipStream_t s);
 hipError_t launch_fill_zero(float* dst, size_t n_floats, hipStream_t s);
 
+// Device address, on the current device, of the library's fixed scratch array of kStaticScratchBytes bytes (256-byte
+// aligned; part of the code object, never allocated or freed; every device holds its own copy, which keeps the contents
+// of the last call).  Looks the address up on the first call per device; allocates nothing.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+hipError_t static_scratch(float** ptr);
+
 // Device-rate probes: `workgroups` x 4 waves each issuing 4*iters fp32 32x32x2 matrix-core instructions
 // (out: workgroups*256 floats), and a 16-byte-per-lane copy of n_floats (multiple of 4, 16-byte aligned).
 hipError_t launch_mfma_issue(float* out, int workgroups, int iters, hipStream_t s);

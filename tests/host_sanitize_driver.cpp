@@ -94,6 +94,19 @@ int main()
     mnn_measure_device_peaks(nullptr, nullptr);
     for (int prec = -1; prec < 4; ++prec)
         for (int v = -1; v < mnn_gemm_variant_count(prec) + 1; ++v) mnn_gemm_variant_name(prec, v);
+    // the calls that prepare weights or run without a plan: no device here, every path must fail cleanly
+    mnn_conv_set_weights(nullptr, nullptr, nullptr);
+    {
+        float dummy[4] = {};
+        mnn_conv_shape sh{1, 4, 9, 9, 4, 3, 3};
+        mnn_conv_geom ge{1, 1, 1, 1, 1, 1};
+        for (int tile = -1; tile <= 9; ++tile) mnn_conv_run_static(&sh, &ge, tile, dummy, dummy, nullptr, dummy, nullptr);
+        mnn_conv_shape big{16, 256, 128, 128, 256, 3, 3};
+        int rcs = mnn_conv_run_static(&big, &ge, 4, dummy, dummy, nullptr, dummy, nullptr);
+        if (rcs != MNN_E_UNSUPPORTED) { std::printf("static entry point accepted a layer beyond its scratch array (%d)\n", rcs); return 1; }
+        mnn_conv_run_static(nullptr, nullptr, 2, nullptr, nullptr, nullptr, nullptr, nullptr);
+        if (mnn_conv_static_scratch_bytes() != ((size_t)64 << 20)) return 1;
+    }
     mnn_chain_t ch = nullptr;
     mnn_chain_create(nullptr, 0, nullptr, nullptr, &ch);
     mnn_chain_layer cl[2] = {};
