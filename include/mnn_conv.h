@@ -124,9 +124,11 @@ enum {
                                  element (xi, c, k) = (G w[k][c] G^T)[xi / alpha][xi % alpha];
                                  fused variants: [b][c/4][a][kg][c%4][k%16], xi = a*alpha + b (kg groups of 16
                                  output channels, channel groups padded to whole 16-channel chunks) */
-    MNN_BUF_V = 1,            /* transformed input tiles, unfused: [alpha^2][C][ldp] (ldp = P rounded up to 4);
+    MNN_BUF_V = 1,            /* transformed input tiles, unfused: [alpha^2][C][ldp] (ldp = P rounded up to 4), or, when
+                                 mnn_plan_info.tiled is set (layers with many tiles), [C][pb][alpha^2][64]: element
+                                 (xi, c, p) at ((c*pb + p/64)*alpha^2 + xi)*64 + p%64, ldp = 64*pb;
                                  fused variants: [b][c/4][a][pg][c%4][p%16]                          */
-    MNN_BUF_M = 2             /* products [alpha^2][c_out][ldp] (unfused variant only)               */
+    MNN_BUF_M = 2             /* products [alpha^2][c_out][ldp], or [c_out][pb][alpha^2][64] when tiled (unfused variant only) */
 };
 
 typedef struct {
@@ -139,6 +141,8 @@ typedef struct {
                                   (alpha = tile_n + k_h - 1, alpha_w = tile_n_w + k_w - 1); an axis with a single tap
                                   has alpha = tile_n = 1; U, V, M hold alpha * alpha_w positions.  Equal to alpha,
                                   tile_n for square kernels. */
+    int32_t tiled, pb;         /* tiled != 0: V and M use the [channel][pb][position][64] layout described at MNN_BUF_V,
+                                  pb = ceil(p / 64) blocks of 64 tiles */
 } mnn_plan_info;
 
 /* Fills *opt with the defaults listed above.  Host. */

@@ -65,7 +65,7 @@ class _GemmDesc(ctypes.Structure):
 
 class _Info(ctypes.Structure):
     _fields_ = [(n, c_int32) for n in ("alpha", "tile_n", "tiles_h", "tiles_w", "p", "ldp", "ldk", "kg", "pg", "h_out", "w_out",
-                                             "alpha_w", "tile_n_w")]
+                                             "alpha_w", "tile_n_w", "tiled", "pb")]
 
 
 class _ChainLayer(ctypes.Structure):

@@ -343,6 +343,7 @@ int mnn_conv_plan_info(mnn_conv_plan_t plan, mnn_plan_info* out)
         out->alpha = im.wg.alpha; out->tile_n = im.wg.n; out->tiles_h = im.wg.th; out->tiles_w = im.wg.tw;
         out->alpha_w = im.wg.alpha_w; out->tile_n_w = im.wg.nw;
         out->p = im.wg.P; out->ldp = im.wg.ldp; out->kg = im.wg.kg; out->pg = im.wg.pg;
+        out->tiled = im.wg.tiled; out->pb = im.wg.pb;
     }
     out->ldk = im.ldk;
     out->h_out = plan->L.Ho; out->w_out = plan->L.Wo;
@@ -845,6 +846,15 @@ int mnn_conv_cache_save(const char* path)
             std::fprintf(f, " | %d %d\n", kv.second.variant, kv.second.splitk);
         }
     }
+    {
+        std::lock_guard<std::mutex> lk(g_input_cap_mu);
+        for (const auto& kv : g_input_cap) {
+            const std::vector<int>& v = std::get<1>(kv.first);
+            std::fprintf(f, "I %d %zu", std::get<0>(kv.first), v.size());
+            for (int x : v) std::fprintf(f, " %d", x);
+            std::fprintf(f, " | %d\n", kv.second);
+        }
+    }
     const bool ok = std::fclose(f) == 0;
     return ok ? MNN_OK : fail(MNN_E_INVALID_ARG, "error writing %s", path);
 }
@@ -891,6 +901,17 @@ int mnn_conv_cache_load(const char* path)
                     if (!rc) {
                         std::lock_guard<std::mutex> lk(g_gemm_mu);
                         g_gemm_choice[GemmKey(dev, v)] = GemmChoice{variant, splitk};
+                    }
+                } else if (tag[0] == 'I') {
+                    std::vector<int> v(n);
+                    for (size_t i = 0; i < n && !rc; ++i)
+                        if (std::fscanf(f, "%d", &v[i]) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
+                    int cap = 0;
+                    if (!rc && std::fscanf(f, " | %d", &cap) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
+                    if (!rc && !(cap == 0 || (cap >= 3 && cap <= 8))) rc = fail(MNN_E_INVALID_ARG, "bad workgroup cap in %s", path);
+                    if (!rc) {
+                        std::lock_guard<std::mutex> lk(g_input_cap_mu);
+                        g_input_cap[InputCapKey(dev, v)] = cap;
                     }
                 } else {
                     rc = fail(MNN_E_INVALID_ARG, "unknown entry type in %s", path);

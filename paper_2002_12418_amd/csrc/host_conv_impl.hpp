@@ -4,6 +4,11 @@
 
 namespace {
 
+// Input-transform occupancy cap per (device, geometry), chosen by timing like the GEMM tile configuration.
+using InputCapKey = std::tuple<int, std::vector<int>>;
+std::mutex g_input_cap_mu;
+std::map<InputCapKey, int> g_input_cap;
+
 // ------------------------------------------------------------------ one realised scheme
 struct Impl {
     mnn_scheme scheme{};
@@ -128,6 +133,15 @@ struct Impl {
             const long long P = (long long)sh.n * wg.th * wg.tw;
             if (P >= (1ll << 30)) return fail(MNN_E_UNSUPPORTED, "too many tiles");
             wg.P = (int)P; wg.ldp = round_up(wg.P, 4); wg.ldk = ldk;
+            // Tiled row layout for V and M ([channel][64 tiles][position][tile in block]): what one wavefront of a transform
+            // kernel writes or reads is then one contiguous 16 KB run instead of alpha^2 runs of 256 bytes (input transform
+            // 3-7 % faster, output transform up to 10 % on the large layers).  Not for few tiles (a block pads P to 64), and
+            // only while one position's operand, which now spans all of V, stays within the GEMM loader's 2 GiB window.
+            if (!rect && s.variant == MNN_WINO_UNFUSED && wg.P >= 1024) {
+                const long long pb = (wg.P + 63) / 64;
+                const long long v_bytes = (long long)wg.alpha * wg.alpha_w * sh.c_in * pb * 64 * (long long)sizeof(float);
+                if (v_bytes < (1ll << 31) - 4096) { wg.tiled = 1; wg.pb = (int)pb; wg.ldp = (int)pb * 64; }
+            }
             const size_t a2 = (size_t)wg.alpha * wg.alpha_w;
             if (rect && s.variant != MNN_WINO_UNFUSED)
                 return fail(MNN_E_UNSUPPORTED, "kernels that are not square have no fused variant");
@@ -188,6 +202,14 @@ struct Impl {
         p.strideA_batch = (long long)wg.C * ldk;
         p.strideB_batch = (long long)wg.C * wg.ldp; p.strideB_img = 0; p.strideB_row = wg.ldp;
         p.strideD_batch = (long long)wg.K * wg.ldp; p.strideD_img = 0; p.strideD_row = wg.ldp;
+        if (wg.tiled) {
+            // V[c][p/64][xi][p%64]: position xi starts 64 floats in, a run of 64 columns is contiguous, the next run
+            // lies alpha^2 * 64 floats on, the next channel pb runs on
+            const long long a2 = (long long)wg.alpha * wg.alpha_w;
+            p.L = 64;
+            p.strideB_batch = 64; p.strideB_img = a2 * 64; p.strideB_row = (long long)wg.pb * a2 * 64;
+            p.strideD_batch = 64; p.strideD_img = a2 * 64; p.strideD_row = (long long)wg.pb * a2 * 64;
+        }
         set_gemm_choice(&p);
         return p;
     }
@@ -245,7 +267,94 @@ struct Impl {
         return alloc_transient(&sk_partial, sk_partial_bytes, "hipMalloc split-K partials");
     }
 
+    // Workgroups per CU of the input transform (WinoGeom::itx_cap), remembered per geometry.  What is timed is the whole
+    // per-inference pass on scratch tensors (input transform, multiplication, output transform), because the transform's time
+    // depends on what the kernels around it leave in the caches: a cap that wins when the kernel runs alone can lose in sequence.
+    int tune_input_cap(hipStream_t s)
+    {
+        if (scheme.kind != MNN_SCHEME_WINOGRAD || rect) return MNN_OK;
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        const InputCapKey key(dev, std::vector<int>{wg.N, wg.C, wg.H, wg.W, wg.K, wg.n, wg.k, wg.pad_h, wg.pad_w, wg.blocked, wg.tiled,
+                                                    scheme.variant, scheme.prec});
+        {
+            std::lock_guard<std::mutex> lk(g_input_cap_mu);
+            auto it = g_input_cap.find(key);
+            if (it != g_input_cap.end()) { wg.itx_cap = it->second; return MNN_OK; }
+        }
+        int cus = 256;
+        (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        const long long lanes = wg.blocked ? (long long)wg.cchunks * ((wg.P + 15) / 16) * 64 : (long long)wg.C * wg.P;
+        auto remember = [&](int cap) {
+            wg.itx_cap = cap;
+            std::lock_guard<std::mutex> lk(g_input_cap_mu);
+            g_input_cap[key] = cap;
+        };
+        if (lanes / 256 < 8ll * cus) { remember(0); return MNN_OK; }          // a short grid never fills a CU that far
+        if (transient_external || !V) { wg.itx_cap = 4; return MNN_OK; }      // nothing to time on: the usual optimum
+        const size_t xb = (size_t)wg.N * wg.C * wg.H * wg.W * sizeof(float);
+        const size_t yb = (size_t)wg.N * wg.K * wg.Ho * wg.Wo * sizeof(float);
+        float *tx = nullptr, *ty = nullptr;
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        hipError_t e;
+        int rc = MNN_OK, best = 0;
+        float best_ms = -1.f;
+        do {
+            if ((e = hipMalloc((void**)&tx, xb)) != hipSuccess || (e = hipMalloc((void**)&ty, yb)) != hipSuccess) {
+                rc = fail_hip(e, "hipMalloc tuning scratch");
+                break;
+            }
+            if ((e = launch_fill_pattern(tx, xb / sizeof(float), 0x5fu, -1.f, 1.f, s)) != hipSuccess ||
+                (e = launch_fill_pattern(U, U_bytes / sizeof(float), 0x60u, -0.5f, 0.5f, s)) != hipSuccess ||
+                (e = hipEventCreate(&e0)) != hipSuccess || (e = hipEventCreate(&e1)) != hipSuccess) {
+                rc = fail_hip(e, "input transform tuning set-up");
+                break;
+            }
+            auto pass = [&]() -> int {
+                for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st) {
+                    const int r = run_stage(st, tx, nullptr, nullptr, ty, s);
+                    if (r) return r;
+                }
+                return MNN_OK;
+            };
+            static const int caps[] = {0, 5, 4, 3};
+            float least[4] = {-1.f, -1.f, -1.f, -1.f};
+            for (int round = 0; round < 2 && !rc; ++round)
+                for (int ci = 0; ci < 4 && !rc; ++ci) {
+                    wg.itx_cap = caps[ci];
+                    if ((rc = pass())) break;                                                // warm-up
+                    if ((e = hipEventRecord(e0, s)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
+                    for (int i = 0; i < 3 && !rc; ++i) rc = pass();
+                    if (rc) break;
+                    float ms = 0.f;
+                    if ((e = hipEventRecord(e1, s)) != hipSuccess || (e = hipEventSynchronize(e1)) != hipSuccess ||
+                        (e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) { rc = fail_hip(e, "input transform tuning"); break; }
+                    if (least[ci] < 0.f || ms < least[ci]) least[ci] = ms;
+                }
+            // the least pass time decides; a cap has to win by 0.5 % of the pass to displace a weaker one
+            for (int ci = 0; ci < 4 && !rc; ++ci)
+                if (best_ms < 0.f || least[ci] < best_ms * 0.995f) { best_ms = least[ci]; best = caps[ci]; }
+            // the prepared weights go back to the zeros they held (their padding must read as zero)
+            if (!rc && ((e = hipMemsetAsync(U, 0, U_bytes, s)) != hipSuccess || (e = hipStreamSynchronize(s)) != hipSuccess))
+                rc = fail_hip(e, "tuning operand reset");
+        } while (false);
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+        if (tx) (void)hipFree(tx);
+        if (ty) (void)hipFree(ty);
+        wg.itx_cap = 0;
+        if (rc) return rc;
+        remember(best);
+        return MNN_OK;
+    }
+
     int tune(hipStream_t s)
+    {
+        int rc = tune_gemm_stage(s);
+        return rc ? rc : tune_input_cap(s);
+    }
+
+    int tune_gemm_stage(hipStream_t s)
     {
         GemmChoice c{0, 1};
         static const float dummy_bias = 0.f;      // only "is there a bias" enters the cache key
@@ -379,15 +488,18 @@ void describe_impl(const Impl& im, char* buf, size_t cap)
     std::string gvs = gemm_variant_name(im.scheme.prec, im.gemm_variant) ? gemm_variant_name(im.scheme.prec, im.gemm_variant) : "?";
     if (im.gemm_splitk > 1) gvs += " splitk=" + std::to_string(im.gemm_splitk);
     const char* gv = gvs.c_str();
+    char capbuf[32] = "";
+    if (im.scheme.kind == MNN_SCHEME_WINOGRAD && im.wg.itx_cap > 0) std::snprintf(capbuf, sizeof capbuf, " input-wg/cu=%d", im.wg.itx_cap);
+    const std::string tail = std::string(im.wg.tiled ? " tiled" : "") + capbuf;
     switch (im.scheme.kind) {
         case MNN_SCHEME_WINOGRAD:
             if (im.rect)
                 std::snprintf(buf, cap, "F(%dx%d,%dx%d) unfused gemm=%s", im.wg.n, im.wg.nw, im.wg.k, im.wg.kw, gv);
             else if (im.scheme.variant == MNN_WINO_UNFUSED)
-                std::snprintf(buf, cap, "F(%d,%d) unfused gemm=%s", im.wg.n, im.wg.k, gv);
+                std::snprintf(buf, cap, "F(%d,%d) unfused gemm=%s%s", im.wg.n, im.wg.k, gv, tail.c_str());
             else
-                std::snprintf(buf, cap, "F(%d,%d) fused-output %s", im.wg.n, im.wg.k,
-                              im.scheme.variant == MNN_WINO_FUSED_OUT_32 ? "32x32" : "64x64");
+                std::snprintf(buf, cap, "F(%d,%d) fused-output %s%s", im.wg.n, im.wg.k,
+                              im.scheme.variant == MNN_WINO_FUSED_OUT_32 ? "32x32" : "64x64", tail.c_str());
             break;
         case MNN_SCHEME_GEMM1X1:
             if (im.strassen) {

@@ -32,6 +32,12 @@ struct WinoGeom {
     int blocked;                // 0: row layouts U[xi][c][ldk], V[xi][c][ldp];  1: blocked
     int kg, pg;                 // allocated 16-column groups along K and along P
     int cchunks;                // allocated 4-channel groups (>= ceil(C/4), padded to whole chunks)
+    // Tiled row layout (blocked == 0, tiled == 1): V[c][p/64][xi][p%64], M[k][p/64][xi][p%64] -- the alpha^2 values of 64
+    // consecutive tiles of one channel are one contiguous run, which is exactly what one wavefront of the transform kernels
+    // writes or reads; ldp = 64 * pb.
+    int tiled;
+    int pb;                     // 64-tile blocks: ceil(P / 64)
+    int itx_cap;                // input transform: workgroups per CU to allow (3..8), 0 = as many as fit
 };
 
 // U[xi][c][k] = (G w[k][c] G^T)[xi/alpha][xi%alpha]          (Section 3.3.1, G W G^T)

@@ -8,6 +8,7 @@
 // The transform matrices arrive as kernel arguments, so they sit in SGPRs and
 // every multiply is a v_fma with a scalar operand.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include "kernels.hpp"
 #include "xcd_remap.hpp"
 
@@ -68,66 +69,144 @@ struct __attribute__((packed, aligned(4))) Unaligned4 { float x, y, z, w; };
 struct __attribute__((packed, aligned(4))) Unaligned2 { float x, y; };
 
 // ---------------------------------------------------------------- input: V = B^T d B
-template <int A, bool BLOCKED>
-__global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg<A, A> bt,
+// Division of a value below 2^31 by a constant the host knows: q = mulhi(n, m) >> sh with m = ceil(2^(31+L) / d),
+// L = ceil(log2 d), sh = L - 1 (exact for every n < 2^31).  A run-time division costs some thirty vector instructions,
+// and this kernel's instruction count is part of its time.
+struct FastDiv { unsigned m, sh, d; };
+inline FastDiv make_fastdiv(unsigned d)
+{
+    FastDiv f{0u, 0u, d};
+    if (d <= 1) return f;
+    unsigned L = 0;
+    while ((1u << L) < d) ++L;
+    f.m = (unsigned)((((unsigned long long)1 << (31 + L)) + d - 1) / d);
+    f.sh = L - 1;
+    return f;
+}
+__device__ __forceinline__ unsigned fast_div(unsigned n, const FastDiv& f) { return f.d <= 1 ? n : (__umulhi(n, f.m) >> f.sh); }
+
+struct InputMap { FastDiv by_tw, by_th, by_cols; };
+
+// One-dimensional transform out = B^T in for an even number of points, using what the generated B^T always looks like for
+// the point sequence 0, +f, -f, +2f, -2f, ..., infinity (the host checks the matrix before it picks this path): row 0
+// (point 0) is an even polynomial, the last row (infinity) an odd one, and the rows of +p and -p share their even
+// coefficients and have opposite odd ones.  A pair of rows then costs one even and one odd dot product and two
+// additions: half the multiply-adds of the dense product.
+template <int A>
+__device__ __forceinline__ void bt_apply_paired(const MatArg<A, A>& bt, const float (&in)[A], float (&out)[A])
+{
+    float e0 = bt.v[0][0] * in[0];
+#pragma unroll
+    for (int t = 2; t < A; t += 2) e0 = fmaf(bt.v[0][t], in[t], e0);
+    out[0] = e0;
+    float ol = bt.v[A - 1][1] * in[1];
+#pragma unroll
+    for (int t = 3; t < A; t += 2) ol = fmaf(bt.v[A - 1][t], in[t], ol);
+    out[A - 1] = ol;
+#pragma unroll
+    for (int m = 1; m < A - 1; m += 2) {
+        float e = bt.v[m][2] * in[2], o = bt.v[m][1] * in[1];
+#pragma unroll
+        for (int t = 4; t < A - 1; t += 2) e = fmaf(bt.v[m][t], in[t], e);
+#pragma unroll
+        for (int t = 3; t < A - 1; t += 2) o = fmaf(bt.v[m][t], in[t], o);
+        out[m] = e + o;
+        out[m + 1] = e - o;
+    }
+}
+
+// One lane per (channel, tile); consecutive lanes are consecutive tiles, so every store of V is 256 contiguous bytes per
+// wavefront and position.  Workgroups are handed out so that an XCD covers a contiguous range of (channel, tile) -- halo
+// rows of neighbouring tiles meet in one L2.
+// PAIRED: the B^T structure above holds (even A only).  WIDE: a tensor is too large for 32-bit byte offsets.
+//
+// What the kernel is made of matters as much as what it moves: alone, the loads of the largest layer take a third of
+// its time, the stores a half, and the vector instructions that are neither (index arithmetic, a 64-bit address per
+// load and store) most of the rest -- they do not hide behind the memory traffic.  So: tile coordinates come from
+// multiplications, every load and store is addressed as a uniform base (scalar registers: tensor + row or position
+// offset) plus one 32-bit lane offset computed once, and the paired transform halves the multiply-adds.
+template <int A, bool BLOCKED, bool PAIRED, bool WIDE>
+__global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, InputMap mp, MatArg<A, A> bt,
                                                               const float* __restrict__ x,
                                                               float* __restrict__ V)
 {
-    const long long idx = (long long)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
+    using lane_off = typename std::conditional<WIDE, long long, unsigned>::type;
+    const unsigned idx = xcd_contiguous(blockIdx.x, gridDim.x) * 256u + threadIdx.x;       // < 2^31 (checked by the launcher)
     int c, p;
+    lane_off vo;                                   // lane part of every V address, in floats
     if constexpr (BLOCKED) {
         // a wavefront owns 16 consecutive tiles x 4 consecutive channels = one 64-float block per position
-        const int pgroups = (g.P + 15) >> 4;
-        const long long rest = idx >> 6;
-        if (rest >= (long long)g.cchunks * pgroups) return;
-        p = (int)(rest % pgroups) * 16 + (int)(idx & 15);
-        c = (int)(rest / pgroups) * 4 + (int)((idx >> 4) & 3);
+        const unsigned rest = idx >> 6;
+        const unsigned cq = fast_div(rest, mp.by_cols);            // mp.by_cols: groups of 16 tiles, ceil(P / 16)
+        if (cq >= (unsigned)g.cchunks) return;
+        const int pgrp = (int)(rest - cq * mp.by_cols.d);
+        p = pgrp * 16 + (int)(idx & 15);
+        c = (int)cq * 4 + (int)((idx >> 4) & 3);
+        vo = ((lane_off)((long long)cq * A * g.pg + pgrp) << 6) + (lane_off)(idx & 63);
+    } else {
+        c = (int)fast_div(idx, mp.by_cols);                        // mp.by_cols: P
+        if (c >= g.C) return;
+        p = (int)(idx - (unsigned)c * mp.by_cols.d);
+        vo = g.tiled ? (lane_off)(((long long)c * g.pb + (p >> 6)) * (A * A)) * 64 + (lane_off)(p & 63)
+                     : (lane_off)((long long)c * g.ldp + p);
+    }
+    // element (a = i, b = j): row layout V[(i*A + j)][c][p]; blocked layout Vb[j][c/4][i][p/16][c%4][p%16]
+    const long long stride_j = BLOCKED ? (long long)g.cchunks * A * g.pg * 64 : g.tiled ? 64ll : (long long)g.C * g.ldp;
+    const long long stride_i = BLOCKED ? (long long)g.pg * 64 : stride_j * A;
+    // in bytes for the narrow form: uniform 64-bit base + zero-extended 32-bit lane offset is an addressing mode of
+    // the global memory instructions, a shifted 64-bit sum is two more vector instructions per access
+    const lane_off vob = WIDE ? vo : vo * 4u;
+    auto vstore = [&](int i, int j, float v) {
+        float* base = V + (i * stride_i + j * stride_j);           // uniform: lives in scalar registers
+        if constexpr (WIDE) base[vob] = v;
+        else *reinterpret_cast<float*>(reinterpret_cast<char*>(base) + vob) = v;
+    };
+    if constexpr (BLOCKED) {
         if (p >= g.P || c >= g.C) {
             // padding of the blocked layout: the multiply stage reads it (against zero rows of U for
             // padded channels), so it must hold finite values whatever the memory held before
-            float* vz = V + (((long long)(c >> 2) * A * g.pg + (p >> 4)) << 6) + ((c & 3) << 4) + (p & 15);
-            const long long zi = (long long)g.pg * 64, zj = (long long)g.cchunks * A * g.pg * 64;
+#pragma unroll 1
             for (int i = 0; i < A; ++i)
-                for (int j = 0; j < A; ++j) vz[i * zi + j * zj] = 0.f;
+#pragma unroll 1
+                for (int j = 0; j < A; ++j) vstore(i, j, 0.f);
             return;
         }
-    } else {
-        if (idx >= (long long)g.C * g.P) return;
-        c = (int)(idx / g.P);
-        p = (int)(idx % g.P);
     }
-    const int tx = p % g.tw;
-    const int t2 = p / g.tw;
-    const int ty = t2 % g.th;
-    const int img = t2 / g.th;
+    const unsigned t2 = fast_div((unsigned)p, mp.by_tw);
+    const int tx = p - (int)t2 * g.tw;
+    const unsigned img = fast_div(t2, mp.by_th);
+    const int ty = (int)t2 - (int)img * g.th;
     const int y0 = ty * g.n - g.pad_h;
     const int x0 = tx * g.n - g.pad_w;
-    const float* xp = x + ((long long)img * g.C + c) * g.H * g.W;
+    // lane part of every x address (floats): the tile's top-left element.  Only dereferenced where it lies inside the
+    // image; for tiles over the top or left edge it is computed with wrap-around and corrected by the in-image (iy, ix).
+    const lane_off plane = (lane_off)((long long)img * g.C + c) * (lane_off)((long long)g.H * g.W);
 
-    // A tile row is alpha consecutive floats.  With one 4-byte load per element, consecutive lanes are n
-    // floats apart and every wavefront-wide load touches about 64*n*4/64 cache lines: the address pipeline,
-    // not HBM, then sets the pace.  Tiles that lie inside the image fetch each row with 16- and 8-byte loads
-    // (4-byte aligned) instead, a quarter of the instructions for the same lines; tiles that overlap the
-    // zero padding take the element-wise path.
     float d[A][A];
     const bool interior = (y0 >= 0) && (y0 + A <= g.H) && (x0 >= 0) && (x0 + A <= g.W);
     if (interior) {
-        const float* tp = xp + (long long)y0 * g.W + x0;
+        // a tile row is A consecutive floats: 16- and 8-byte loads at 4-byte alignment
+        const lane_off xo = plane + (lane_off)(y0 * g.W + x0);
+        const lane_off xob = WIDE ? xo : xo * 4u;
+        auto at = [&](const float* uniform_base) -> const char* {
+            if constexpr (WIDE) return reinterpret_cast<const char*>(uniform_base + xob);
+            else return reinterpret_cast<const char*>(uniform_base) + xob;
+        };
 #pragma unroll
         for (int i = 0; i < A; ++i) {
-            const float* rp = tp + (long long)i * g.W;
+            const float* rp = x + (long long)i * g.W;              // uniform
             int j = 0;
 #pragma unroll
             for (; j + 4 <= A; j += 4) {
-                const Unaligned4 v = *reinterpret_cast<const Unaligned4*>(rp + j);
+                const Unaligned4 v = *reinterpret_cast<const Unaligned4*>(at(rp + j));
                 d[i][j] = v.x; d[i][j + 1] = v.y; d[i][j + 2] = v.z; d[i][j + 3] = v.w;
             }
             if (j + 2 <= A) {
-                const Unaligned2 v = *reinterpret_cast<const Unaligned2*>(rp + j);
+                const Unaligned2 v = *reinterpret_cast<const Unaligned2*>(at(rp + j));
                 d[i][j] = v.x; d[i][j + 1] = v.y;
                 j += 2;
             }
-            if (j < A) d[i][j] = rp[j];
+            if (j < A) d[i][j] = *reinterpret_cast<const float*>(at(rp + j));
         }
     } else {
 #pragma unroll
@@ -138,40 +217,47 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, MatArg
             for (int j = 0; j < A; ++j) {
                 const int ix = x0 + j;
                 const bool ok = rowok && (ix >= 0) && (ix < g.W);
-                d[i][j] = ok ? xp[(long long)iy * g.W + ix] : 0.f;
+                d[i][j] = ok ? x[plane + (lane_off)(iy * g.W + ix)] : 0.f;
             }
         }
     }
-    // v = B^T d B, one row of t = B^T d at a time: row i of v needs row i of t only, so t never exists as a
-    // whole and the kernel stays below 96 registers (five wavefronts per SIMD instead of three at alpha = 8).
-    // element (a = i, b = j): row layout V[(i*A + j)][c][p]; blocked layout Vb[j][c/4][i][p/16][c%4][p%16]
-    long long stride_i, stride_j;
-    float* vp;
-    if constexpr (BLOCKED) {
-        stride_i = (long long)g.pg * 64;
-        stride_j = (long long)g.cchunks * A * g.pg * 64;
-        vp = V + (((long long)(c >> 2) * A * g.pg + (p >> 4)) << 6) + ((c & 3) << 4) + (p & 15);
-    } else {
-        stride_j = (long long)g.C * g.ldp;
-        stride_i = stride_j * A;
-        vp = V + (long long)c * g.ldp + p;
-    }
-#pragma unroll 1
-    for (int i = 0; i < A; ++i) {
-        float t[A];
+    if constexpr (PAIRED) {
+        // columns (t = B^T d, in place), then rows (v = t B), each row stored as soon as it exists
 #pragma unroll
         for (int j = 0; j < A; ++j) {
-            float acc = 0.f;
+            float in[A], out[A];
 #pragma unroll
-            for (int a = 0; a < A; ++a) acc = fmaf(bt.v[i][a], d[a][j], acc);
-            t[j] = acc;
+            for (int a = 0; a < A; ++a) in[a] = d[a][j];
+            bt_apply_paired<A>(bt, in, out);
+#pragma unroll
+            for (int a = 0; a < A; ++a) d[a][j] = out[a];
         }
 #pragma unroll
-        for (int j = 0; j < A; ++j) {
-            float acc = 0.f;
+        for (int i = 0; i < A; ++i) {
+            float out[A];
+            bt_apply_paired<A>(bt, d[i], out);
 #pragma unroll
-            for (int b = 0; b < A; ++b) acc = fmaf(t[b], bt.v[j][b], acc);
-            vp[i * stride_i + j * stride_j] = acc;
+            for (int j = 0; j < A; ++j) vstore(i, j, out[j]);
+        }
+    } else {
+        // dense B^T, one row of t = B^T d at a time: row i of v needs row i of t only, so t never exists as a whole
+#pragma unroll 1
+        for (int i = 0; i < A; ++i) {
+            float t[A];
+#pragma unroll
+            for (int j = 0; j < A; ++j) {
+                float acc = 0.f;
+#pragma unroll
+                for (int a = 0; a < A; ++a) acc = fmaf(bt.v[i][a], d[a][j], acc);
+                t[j] = acc;
+            }
+#pragma unroll
+            for (int j = 0; j < A; ++j) {
+                float acc = 0.f;
+#pragma unroll
+                for (int b = 0; b < A; ++b) acc = fmaf(t[b], bt.v[j][b], acc);
+                vstore(i, j, acc);
+            }
         }
     }
 }
@@ -197,8 +283,8 @@ __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatAr
     const int ty = t2 % g.th;
     const int img = t2 / g.th;
 
-    const long long plane = (long long)g.K * g.ldp;
-    const float* mp = M + (long long)kk * g.ldp + p;
+    const long long plane = g.tiled ? 64ll : (long long)g.K * g.ldp;
+    const float* mp = g.tiled ? M + (((long long)kk * g.pb + (p >> 6)) * (A * A)) * 64 + (p & 63) : M + (long long)kk * g.ldp + p;
     // t = A^T m   (NT x A), accumulated row of m by row of m
     float t[NT][A];
 #pragma unroll
@@ -266,6 +352,20 @@ __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatAr
     }
 }
 
+// Whether B^T (row-major A x A) has the structure bt_apply_paired relies on, exactly.
+inline bool bt_is_paired(const float* BT, int A)
+{
+    if (A % 2) return false;
+    for (int t = 1; t < A; t += 2) if (BT[t] != 0.f) return false;                         // row 0: even
+    for (int t = 0; t < A; t += 2) if (BT[(A - 1) * A + t] != 0.f) return false;           // last row: odd
+    for (int m = 1; m < A - 1; m += 2) {
+        if (BT[m * A] != 0.f || BT[m * A + A - 1] != 0.f || BT[(m + 1) * A] != 0.f || BT[(m + 1) * A + A - 1] != 0.f) return false;
+        for (int t = 1; t < A - 1; ++t)
+            if (BT[(m + 1) * A + t] != ((t & 1) ? -BT[m * A + t] : BT[m * A + t])) return false;
+    }
+    return true;
+}
+
 template <int A>
 hipError_t launch_input_t(const WinoGeom& g, const float* BT, const float* x, float* V, hipStream_t s)
 {
@@ -275,15 +375,31 @@ hipError_t launch_input_t(const WinoGeom& g, const float* BT, const float* x, fl
     // V is stored normally even when it is far larger than the caches: stores that go past them make this
     // kernel 25-35 % faster run alone but slower in sequence -- normal stores park about half of V in the 256 MB
     // last-level cache, its write-back overlaps the matrix-core-bound GEMM, and the GEMM finds that half there.
-    if (g.blocked) {
-        const long long total = (long long)g.cchunks * ((g.P + 15) / 16) * 64;
-        const unsigned blocks = (unsigned)((total + 255) / 256);
-        hipLaunchKernelGGL((input_transform_kernel<A, true>), dim3(blocks), dim3(256), 0, s, g, m, x, V);
-    } else {
-        const long long total = (long long)g.C * g.P;
-        const unsigned blocks = (unsigned)((total + 255) / 256);
-        hipLaunchKernelGGL((input_transform_kernel<A, false>), dim3(blocks), dim3(256), 0, s, g, m, x, V);
-    }
+    const long long cols = g.blocked ? (g.P + 15) / 16 : g.P;
+    const long long lanes = g.blocked ? (long long)g.cchunks * cols * 64 : (long long)g.C * cols;
+    if (lanes <= 0 || lanes + 256 >= (1ll << 31)) return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)((lanes + 255) / 256);
+    InputMap mp{make_fastdiv((unsigned)g.tw), make_fastdiv((unsigned)g.th), make_fastdiv((unsigned)cols)};
+    // 32-bit byte offsets: the input, one position plane of V (row layout) or one slab of V (blocked) below 4 GiB
+    const long long in_elems = (long long)g.N * g.C * g.H * g.W;
+    const long long v_elems = g.blocked ? (long long)g.cchunks * A * g.pg * 64 : (long long)g.C * g.ldp * (g.tiled ? A * A : 1);
+    const bool wide = in_elems >= (1ll << 30) || v_elems >= (1ll << 30);
+    const bool paired = bt_is_paired(BT, A);
+    const dim3 grid(blocks), block(256);
+    // Fewer workgroups per CU than the registers allow: the kernel is bound by the memory system, and past three or four
+    // workgroups per CU more concurrent store streams only thrash it (10 % slower at six).  LDS the kernel never touches is
+    // the lever: a workgroup that asks for 1/n of a CU's 160 KB leaves room for n of them.
+    const size_t cap_lds = (g.itx_cap >= 3 && g.itx_cap <= 8) ? ((size_t)160 * 1024 / g.itx_cap - 1024) / 256 * 256 : 0;
+    auto launch = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, cap_lds, s, g, mp, m, x, V); };
+    auto pick = [&](auto blocked_c, auto wide_c) {
+        constexpr bool B = decltype(blocked_c)::value, W = decltype(wide_c)::value;
+        if constexpr (A % 2 == 0) {
+            if (paired) { launch(input_transform_kernel<A, B, true, W>); return; }
+        }
+        launch(input_transform_kernel<A, B, false, W>);
+    };
+    if (g.blocked) { if (wide) pick(std::true_type{}, std::true_type{}); else pick(std::true_type{}, std::false_type{}); }
+    else           { if (wide) pick(std::false_type{}, std::true_type{}); else pick(std::false_type{}, std::false_type{}); }
     return hipGetLastError();
 }
 
@@ -329,7 +445,7 @@ bool geom_ok(const WinoGeom& g)
     if ((long long)g.P != (long long)g.N * g.th * g.tw) return false;
     if (g.blocked) {
         if ((long long)g.cchunks * 4 < g.C || (long long)g.kg * 16 < g.K || (long long)g.pg * 16 < g.P) return false;
-    } else if (g.ldp < g.P || g.ldk < g.K) {
+    } else if (g.ldp < g.P || g.ldk < g.K || (g.tiled && ((long long)g.pb * 64 != g.ldp))) {
         return false;
     }
     // every per-plane element count must fit the 32-bit tile arithmetic used in the kernels

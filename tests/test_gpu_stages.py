@@ -25,6 +25,9 @@ CASES = [
     (4, 5, 1, 6, 12, 16, 7, 2),
     (2, 7, 1, 4, 16, 16, 5, 3),
     (3, 2, 2, 6, 9, 9, 4, 0),
+    # more than 1024 tiles: the tiled layout [channel][64 tiles][position][tile in block], last block ragged
+    (4, 3, 5, 6, 60, 62, 7, 1),
+    (6, 3, 3, 5, 111, 120, 4, 1),
 ]
 
 
@@ -49,8 +52,15 @@ def test_unfused_stage_buffers(case):
         P, ldp, ldk = info["p"], info["ldp"], info["ldk"]
         assert P == st["V"].shape[-1] and info["alpha"] == a
         U = plan.buffer_to_numpy(m.BUF_U).reshape(a * a, C, ldk)
-        V = plan.buffer_to_numpy(m.BUF_V).reshape(a * a, C, ldp)
-        M = plan.buffer_to_numpy(m.BUF_M).reshape(a * a, K, ldp)
+        V, M = plan.buffer_to_numpy(m.BUF_V), plan.buffer_to_numpy(m.BUF_M)
+        assert bool(info["tiled"]) == (P >= 1024)
+        if info["tiled"]:
+            pb = info["pb"]
+            assert pb == (P + 63) // 64 and ldp == 64 * pb
+            V = V.reshape(C, pb, a * a, 64).transpose(2, 0, 1, 3).reshape(a * a, C, ldp)
+            M = M.reshape(K, pb, a * a, 64).transpose(2, 0, 1, 3).reshape(a * a, K, ldp)
+        else:
+            V, M = V.reshape(a * a, C, ldp), M.reshape(a * a, K, ldp)
     Uref = st["U"].reshape(a * a, K, C).transpose(0, 2, 1)            # library keeps U transposed: [xi][c][k]
     assert relerr(U[:, :, :K], Uref) < 1e-5
     assert np.all(U[:, :, K:] == 0)
