@@ -52,21 +52,26 @@ def stage_work(layer, scheme, info, mnn):
 def recorded_traffic(cfg, kernel_desc):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary
     (profiles/dominant_kernel_traffic.txt, already scaled by the readings of the copy probe; counters cannot be read
-    from inside this process).  None unless that file
-    has a line for this workload whose layer and scheme are those of the kernel found dominant in this very run."""
+    from inside this process).  Returns (bytes, source).  bytes is None unless that file has a line for this workload
+    whose layer, scheme AND GEMM tile configuration are those of the kernel found dominant in this very run (the tile
+    configuration is re-tuned per process; a different one is a different kernel, whose traffic was not recorded)."""
+    import re
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "dominant_kernel_traffic.txt")
 
-    def scheme_of(desc):        # layer and scheme; the GEMM tile configuration is re-tuned per process and moves the same bytes
-        return desc.split(" gemm=")[0]
+    def norm(desc):        # the workgroup cap of the input transform is no property of the GEMM kernel
+        return re.sub(r" input-wg/cu=\d+", "", desc).strip()
+    recorded = ""
     try:
         for line in open(path):
+            if line.startswith("# recorded"):
+                recorded = line[1:].strip()
             f = [t.strip() for t in line.split("|")]
-            if len(f) == 6 and f[0] == f"cfg{cfg}" and scheme_of(f[1]) == scheme_of(kernel_desc):
+            if len(f) == 6 and f[0] == f"cfg{cfg}" and norm(f[1]) == norm(kernel_desc):
                 kib = float(f[4].split()[1]) + float(f[5].split()[1])
-                return round(kib * 1024.0)
+                return round(kib * 1024.0), f"profiles/dominant_kernel_traffic.txt (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, {recorded or 'committed'}; not measured by this run)"
     except (OSError, ValueError, IndexError):
         pass
-    return None
+    return None, "no recorded rocprofv3 counter run matches the kernel this run found dominant (layer, scheme and tile configuration)"
 
 
 def cpu_baseline(layers):
@@ -147,6 +152,7 @@ def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
         sw = stage_work(layer, sch, plan.info, mnn)
         entry = {"layer": layer.name, "scheme": sch.label(layer.k_long), "kernels": plan.describe(),
                  "planner_ms": {c.label(layer.k_long): round(c.est_ms, 4) for c in plan.candidates if c.est_ms >= 0},
+                 "planner_est_ms": round(sch.est_ms, 5) if sch.est_ms >= 0 else None,
                  "stage_ms": {STAGE_NAMES[i]: round(ms[i], 5) for i in range(1, 4) if ms[i] > 0},
                  "filter_ms_one_off": round(ms[0], 5)}
         if layer.kh == layer.kw and layer.kh > 1 and layer.stride == 1 and layer.dil == 1:
@@ -162,6 +168,9 @@ def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
             entry["model_n"] = pred.tile_n if pred.kind == mnn.SCHEME_WINOGRAD else 1
         lay_ms = sum(ms[1:4])
         entry["ms"] = round(lay_ms, 5)
+        if sch.est_ms > 0 and lay_ms > 0:
+            # what pre-inference measured on seeded scratch tensors against what the instrumented pass measures on the workload's
+            entry["planner_est_over_measured"] = round(sch.est_ms / lay_ms, 4)
         entry["gflops_direct_count"] = round(layer.direct_flops / (lay_ms * 1e-3) / 1e9, 1) if lay_ms > 0 else None
         for name, (fl, by) in sw.items():
             i = STAGE_NAMES.index(name)
@@ -358,7 +367,7 @@ def main():
         ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roofline = {"kernel": f"{dom['layer']}: {dom['stage']} of {dom['desc']}", "bound": "hbm", "achieved": round(ach, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
-    roofline["traffic"] = recorded_traffic(args.config, roofline["kernel"])
+    roofline["traffic"], roofline["traffic_source"] = recorded_traffic(args.config, roofline["kernel"])
     roofline["avg_launch_ms"] = round(dom["ms"], 5)
     roofline["algorithmic_flops_per_launch"] = dom["flops"]
     roofline["algorithmic_bytes_per_launch"] = dom["bytes"]

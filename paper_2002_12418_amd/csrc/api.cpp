@@ -826,7 +826,7 @@ int mnn_conv_cache_save(const char* path)
     if (!path) return fail(MNN_E_INVALID_ARG, "path is NULL");
     FILE* f = std::fopen(path, "w");
     if (!f) return fail(MNN_E_INVALID_ARG, "cannot open %s for writing", path);
-    std::fprintf(f, "mnnconv-plan-cache 2\n");
+    std::fprintf(f, "mnnconv-plan-cache 3\n");
     {
         std::lock_guard<std::mutex> lk(g_cache_mu);
         for (const auto& kv : g_cache) {
@@ -867,7 +867,7 @@ int mnn_conv_cache_load(const char* path)
     int version = 0;
     int rc = MNN_OK;
     try {
-        if (std::fscanf(f, "mnnconv-plan-cache %d", &version) != 1 || version != 2) {
+        if (std::fscanf(f, "mnnconv-plan-cache %d", &version) != 1 || version != 3) {
             rc = fail(MNN_E_INVALID_ARG, "%s is not a plan cache of this library", path);
         } else {
             char tag[4];

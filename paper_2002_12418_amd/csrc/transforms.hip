@@ -131,7 +131,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, InputM
                                                               float* __restrict__ V)
 {
     using lane_off = typename std::conditional<WIDE, long long, unsigned>::type;
-    const unsigned idx = xcd_contiguous(blockIdx.x, gridDim.x) * 256u + threadIdx.x;       // < 2^31 (checked by the launcher)
+    const unsigned idx = xcd_contiguous(blockIdx.x, gridDim.x) * blockDim.x + threadIdx.x;       // < 2^31 (checked by the launcher)
     int c, p;
     lane_off vo;                                   // lane part of every V address, in floats
     if constexpr (BLOCKED) {

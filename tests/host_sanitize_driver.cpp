@@ -78,7 +78,7 @@ int main()
     mnn_conv_cache_save(path);
     mnn_conv_cache_load(path);
     FILE* f = std::fopen(path, "w");
-    std::fprintf(f, "mnnconv-plan-cache 2\nS 0 999999999 1 2 3\nG 0 3 1 2\nS 0 16 1 2 3 4 5 6 7 8 9 10 11 12 13 14 15 16 0.5 | 2 4 0 0 0.1\n\x01\x02garbage");
+    std::fprintf(f, "mnnconv-plan-cache 3\nS 0 999999999 1 2 3\nG 0 3 1 2\nS 0 16 1 2 3 4 5 6 7 8 9 10 11 12 13 14 15 16 0.5 | 2 4 0 0 0.1\n\x01\x02garbage");
     std::fclose(f);
     int rc = mnn_conv_cache_load(path);
     std::printf("garbage cache load -> %d (%s)\n", rc, mnn_last_error());

@@ -217,11 +217,11 @@ def test_cache_file_round_trip_rejects_garbage(mnn, tmp_path):
     good = tmp_path / "plans.txt"
     mnn.cache_clear()
     mnn.cache_save(str(good))
-    assert good.read_text().startswith("mnnconv-plan-cache 2")
+    assert good.read_text().startswith("mnnconv-plan-cache 3")
     mnn.cache_load(str(good))
     assert mnn.cache_size() == 0
     # a hand-written entry: device 0, cfg1 layer with the default options, F(4,3) unfused
-    good.write_text("mnnconv-plan-cache 2\nS 0 16 1 16 32 32 16 3 3 1 1 1 1 1 1 8 0 0 0.5 | 2 4 0 0 0.01\n")
+    good.write_text("mnnconv-plan-cache 3\nS 0 16 1 16 32 32 16 3 3 1 1 1 1 1 1 8 0 0 0.5 | 2 4 0 0 0.01\n")
     mnn.cache_load(str(good))
     assert mnn.cache_size() == 1
     mnn.cache_clear()
