@@ -113,3 +113,38 @@ def test_half_points_are_more_accurate_in_float32_than_unit_points():
         return np.max(np.abs(y - ref)) / np.max(np.abs(ref))
 
     assert err(Fr(1, 2)) < 0.2 * err(Fr(1))
+
+
+def _float32_winograd_error(n, k, f, C=64, T=48, seed=7):
+    """max|err| / max|ref| of one Winograd tile computation carried out in float32 with the exact matrices rounded once,
+    against the float64 correlation of the same float32 data: what any float32 implementation of F(n, k) is up against."""
+    AT, G, BT = cook_toom.matrices(n, k, Fr(f).limit_denominator(1000))
+    a = n + k - 1
+    AT32, G32, BT32 = (np.array([[float(v) for v in row] for row in m], np.float32) for m in (AT, G, BT))
+    rng = np.random.default_rng(seed)
+    d = rng.uniform(-1, 1, (T, C, a, a)).astype(np.float32)
+    g = rng.normal(0, np.sqrt(2.0 / (k * k * C)), (C, k, k)).astype(np.float32)
+    U = np.einsum("ik,ckl,jl->cij", G32, g, G32).astype(np.float32)
+    V = np.einsum("ik,tckl,jl->tcij", BT32, d, BT32).astype(np.float32)
+    M = np.einsum("cij,tcij->tij", U, V).astype(np.float32)
+    Y = np.einsum("ik,tkl,jl->tij", AT32, M, AT32).astype(np.float32)
+    ref = np.zeros((T, n, n))
+    for i in range(n):
+        for j in range(n):
+            ref[:, i, j] = np.einsum("tckl,ckl->t", d[:, :, i:i + k, j:j + k].astype(np.float64), g.astype(np.float64))
+    return float(np.abs(Y - ref).max() / np.abs(ref).max())
+
+
+def test_float32_error_bounds_the_usable_tile_sizes():
+    """Why the library stops at alpha = n + k - 1 = 10: in float32 the generated transforms keep the 1e-3 bound up to
+    alpha = 10 and lose it at alpha = 11, for the paper's f = 0.5 and for closer points alike; and why it spaces the
+    points 0.425 apart for alpha = 9, 10 when asked to choose (several times less error than 0.5, the reverse at 8)."""
+    for n, k in ((6, 3), (4, 5), (2, 7)):
+        assert _float32_winograd_error(n, k, 0.5) < 1e-4                      # alpha = 8
+    for n, k in ((7, 3), (8, 3), (6, 5), (4, 7)):                               # alpha = 9, 10
+        e5, e4 = _float32_winograd_error(n, k, 0.5), _float32_winograd_error(n, k, 0.425)
+        assert e5 < 1e-3 and e4 < 3e-4 and e4 < 0.7 * e5
+    for n, k in ((9, 3), (5, 7), (10, 3)):                                     # alpha = 11, 12
+        assert _float32_winograd_error(n, k, 0.5) > 5e-3
+        assert _float32_winograd_error(n, k, 0.425) > 1e-3
+    assert _float32_winograd_error(6, 3, 0.5) < _float32_winograd_error(6, 3, 0.425)
