@@ -59,7 +59,7 @@ def recorded_traffic(cfg, kernel_desc):
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "dominant_kernel_traffic.txt")
 
     def norm(desc):        # the workgroup cap of the input transform is no property of the GEMM kernel
-        return re.sub(r" input-wg/cu=\d+", "", desc).strip()
+        return re.sub(r" input-waves/cu=\d+", "", desc).strip()
     recorded = ""
     try:
         for line in open(path):

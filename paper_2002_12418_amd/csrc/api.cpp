@@ -908,7 +908,7 @@ int mnn_conv_cache_load(const char* path)
                         if (std::fscanf(f, "%d", &v[i]) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
                     int cap = 0;
                     if (!rc && std::fscanf(f, " | %d", &cap) != 1) rc = fail(MNN_E_INVALID_ARG, "malformed entry in %s", path);
-                    if (!rc && !(cap == 0 || (cap >= 3 && cap <= 8))) rc = fail(MNN_E_INVALID_ARG, "bad workgroup cap in %s", path);
+                    if (!rc && !(cap == 0 || (cap >= 8 && cap <= 32))) rc = fail(MNN_E_INVALID_ARG, "bad wavefront cap in %s", path);
                     if (!rc) {
                         std::lock_guard<std::mutex> lk(g_input_cap_mu);
                         g_input_cap[InputCapKey(dev, v)] = cap;

@@ -267,9 +267,11 @@ struct Impl {
         return alloc_transient(&sk_partial, sk_partial_bytes, "hipMalloc split-K partials");
     }
 
-    // Workgroups per CU of the input transform (WinoGeom::itx_cap), remembered per geometry.  What is timed is the whole
-    // per-inference pass on scratch tensors (input transform, multiplication, output transform), because the transform's time
-    // depends on what the kernels around it leave in the caches: a cap that wins when the kernel runs alone can lose in sequence.
+    // Resident wavefronts per CU of the input transform (WinoGeom::itx_waves), remembered per geometry.  What is timed is the
+    // transform inside whole per-inference passes on scratch tensors (input transform, multiplication, output transform), because
+    // its time depends on what the kernels around it leave in the caches: a cap that wins when the kernel runs alone can lose in
+    // sequence.  (The time of the whole pass is no usable criterion where the multiplication dominates: its run-to-run spread
+    // exceeds what the cap moves.)
     int tune_input_cap(hipStream_t s)
     {
         if (scheme.kind != MNN_SCHEME_WINOGRAD || rect) return MNN_OK;
@@ -280,23 +282,24 @@ struct Impl {
         {
             std::lock_guard<std::mutex> lk(g_input_cap_mu);
             auto it = g_input_cap.find(key);
-            if (it != g_input_cap.end()) { wg.itx_cap = it->second; return MNN_OK; }
+            if (it != g_input_cap.end()) { wg.itx_waves = it->second; return MNN_OK; }
         }
         int cus = 256;
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         const long long lanes = wg.blocked ? (long long)wg.cchunks * ((wg.P + 15) / 16) * 64 : (long long)wg.C * wg.P;
         auto remember = [&](int cap) {
-            wg.itx_cap = cap;
+            wg.itx_waves = cap;
             std::lock_guard<std::mutex> lk(g_input_cap_mu);
             g_input_cap[key] = cap;
         };
         if (lanes / 256 < 8ll * cus) { remember(0); return MNN_OK; }          // a short grid never fills a CU that far
-        if (transient_external || !V) { wg.itx_cap = 4; return MNN_OK; }      // nothing to time on: the usual optimum
+        if (transient_external || !V) { wg.itx_waves = 16; return MNN_OK; }      // nothing to time on: the usual optimum
         const size_t xb = (size_t)wg.N * wg.C * wg.H * wg.W * sizeof(float);
         const size_t yb = (size_t)wg.N * wg.K * wg.Ho * wg.Wo * sizeof(float);
         float *tx = nullptr, *ty = nullptr;
-        hipEvent_t e0 = nullptr, e1 = nullptr;
-        hipError_t e;
+        constexpr int kMaxIters = 24;
+        hipEvent_t ev[2 * kMaxIters] = {};
+        hipError_t e = hipSuccess;
         int rc = MNN_OK, best = 0;
         float best_ms = -1.f;
         do {
@@ -305,44 +308,62 @@ struct Impl {
                 break;
             }
             if ((e = launch_fill_pattern(tx, xb / sizeof(float), 0x5fu, -1.f, 1.f, s)) != hipSuccess ||
-                (e = launch_fill_pattern(U, U_bytes / sizeof(float), 0x60u, -0.5f, 0.5f, s)) != hipSuccess ||
-                (e = hipEventCreate(&e0)) != hipSuccess || (e = hipEventCreate(&e1)) != hipSuccess) {
+                (e = launch_fill_pattern(U, U_bytes / sizeof(float), 0x60u, -0.5f, 0.5f, s)) != hipSuccess) {
                 rc = fail_hip(e, "input transform tuning set-up");
                 break;
             }
-            auto pass = [&]() -> int {
-                for (int st = MNN_STAGE_INPUT; st < MNN_STAGE_COUNT; ++st) {
-                    const int r = run_stage(st, tx, nullptr, nullptr, ty, s);
+            for (auto& v : ev)
+                if ((e = hipEventCreate(&v)) != hipSuccess) break;
+            if (e != hipSuccess) { rc = fail_hip(e, "hipEventCreate"); break; }
+            // one measurement: `iters` whole passes back to back (input transform, multiplication, output transform), the
+            // input transform of each bracketed by events; returns the mean time of that stage in its natural surroundings
+            auto measure = [&](int iters, float* stage_ms) -> int {
+                for (int i = 0; i < iters; ++i) {
+                    if ((e = hipEventRecord(ev[2 * i], s)) != hipSuccess) return fail_hip(e, "hipEventRecord");
+                    int r = run_stage(MNN_STAGE_INPUT, tx, nullptr, nullptr, ty, s);
                     if (r) return r;
+                    if ((e = hipEventRecord(ev[2 * i + 1], s)) != hipSuccess) return fail_hip(e, "hipEventRecord");
+                    for (int st = MNN_STAGE_GEMM; st < MNN_STAGE_COUNT; ++st)
+                        if ((r = run_stage(st, tx, nullptr, nullptr, ty, s))) return r;
                 }
+                if ((e = hipStreamSynchronize(s)) != hipSuccess) return fail_hip(e, "hipStreamSynchronize");
+                double sum = 0.0;
+                for (int i = 1; i < iters; ++i) {                                           // the first pass is the warm-up
+                    float ms = 0.f;
+                    if ((e = hipEventElapsedTime(&ms, ev[2 * i], ev[2 * i + 1])) != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
+                    sum += ms;
+                }
+                *stage_ms = (float)(sum / (iters - 1));
                 return MNN_OK;
             };
-            static const int caps[] = {0, 5, 4, 3};
-            float least[4] = {-1.f, -1.f, -1.f, -1.f};
-            for (int round = 0; round < 2 && !rc; ++round)
-                for (int ci = 0; ci < 4 && !rc; ++ci) {
-                    wg.itx_cap = caps[ci];
-                    if ((rc = pass())) break;                                                // warm-up
-                    if ((e = hipEventRecord(e0, s)) != hipSuccess) { rc = fail_hip(e, "hipEventRecord"); break; }
-                    for (int i = 0; i < 3 && !rc; ++i) rc = pass();
-                    if (rc) break;
+            static const int caps[] = {0, 20, 16, 12, 10};
+            const int ncaps = wg.blocked ? 4 : 5;
+            float least[5] = {-1.f, -1.f, -1.f, -1.f, -1.f};
+            // enough passes per measurement for about 1 ms of the stage: short layers are decided by differences of a microsecond
+            float probe = 0.f;
+            wg.itx_waves = 0;
+            if ((rc = measure(4, &probe))) break;
+            int iters = probe > 0.f ? (int)(1.0f / probe) + 1 : kMaxIters;
+            iters = iters < 6 ? 6 : iters > kMaxIters ? kMaxIters : iters;
+            for (int round = 0; round < 3 && !rc; ++round)
+                for (int ci = 0; ci < ncaps && !rc; ++ci) {
+                    wg.itx_waves = caps[ci];
                     float ms = 0.f;
-                    if ((e = hipEventRecord(e1, s)) != hipSuccess || (e = hipEventSynchronize(e1)) != hipSuccess ||
-                        (e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) { rc = fail_hip(e, "input transform tuning"); break; }
+                    if ((rc = measure(iters, &ms))) break;
                     if (least[ci] < 0.f || ms < least[ci]) least[ci] = ms;
                 }
-            // the least pass time decides; a cap has to win by 0.5 % of the pass to displace a weaker one
-            for (int ci = 0; ci < 4 && !rc; ++ci)
-                if (best_ms < 0.f || least[ci] < best_ms * 0.995f) { best_ms = least[ci]; best = caps[ci]; }
+            // the least stage time decides; a cap has to win by 1 % to displace a weaker one
+            for (int ci = 0; ci < ncaps && !rc; ++ci)
+                if (best_ms < 0.f || least[ci] < best_ms * 0.99f) { best_ms = least[ci]; best = caps[ci]; }
             // the prepared weights go back to the zeros they held (their padding must read as zero)
             if (!rc && ((e = hipMemsetAsync(U, 0, U_bytes, s)) != hipSuccess || (e = hipStreamSynchronize(s)) != hipSuccess))
                 rc = fail_hip(e, "tuning operand reset");
         } while (false);
-        if (e0) (void)hipEventDestroy(e0);
-        if (e1) (void)hipEventDestroy(e1);
+        for (auto& v : ev)
+            if (v) (void)hipEventDestroy(v);
         if (tx) (void)hipFree(tx);
         if (ty) (void)hipFree(ty);
-        wg.itx_cap = 0;
+        wg.itx_waves = 0;
         if (rc) return rc;
         remember(best);
         return MNN_OK;
@@ -489,7 +510,7 @@ void describe_impl(const Impl& im, char* buf, size_t cap)
     if (im.gemm_splitk > 1) gvs += " splitk=" + std::to_string(im.gemm_splitk);
     const char* gv = gvs.c_str();
     char capbuf[32] = "";
-    if (im.scheme.kind == MNN_SCHEME_WINOGRAD && im.wg.itx_cap > 0) std::snprintf(capbuf, sizeof capbuf, " input-wg/cu=%d", im.wg.itx_cap);
+    if (im.scheme.kind == MNN_SCHEME_WINOGRAD && im.wg.itx_waves > 0) std::snprintf(capbuf, sizeof capbuf, " input-waves/cu=%d", im.wg.itx_waves);
     const std::string tail = std::string(im.wg.tiled ? " tiled" : "") + capbuf;
     switch (im.scheme.kind) {
         case MNN_SCHEME_WINOGRAD:

@@ -37,7 +37,7 @@ struct WinoGeom {
     // writes or reads; ldp = 64 * pb.
     int tiled;
     int pb;                     // 64-tile blocks: ceil(P / 64)
-    int itx_cap;                // input transform: workgroups per CU to allow (3..8), 0 = as many as fit
+    int itx_waves;              // input transform: resident wavefronts per CU to allow (10, 12, 16 or 20), 0 = as many as fit
 };
 
 // U[xi][c][k] = (G w[k][c] G^T)[xi/alpha][xi%alpha]          (Section 3.3.1, G W G^T)

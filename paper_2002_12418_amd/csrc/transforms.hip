@@ -378,18 +378,25 @@ hipError_t launch_input_t(const WinoGeom& g, const float* BT, const float* x, fl
     const long long cols = g.blocked ? (g.P + 15) / 16 : g.P;
     const long long lanes = g.blocked ? (long long)g.cchunks * cols * 64 : (long long)g.C * cols;
     if (lanes <= 0 || lanes + 256 >= (1ll << 31)) return hipErrorInvalidValue;
-    const unsigned blocks = (unsigned)((lanes + 255) / 256);
+    // Fewer wavefronts per CU than the registers allow: the kernel is bound by the memory system, and past 10 to 16 resident
+    // wavefronts per CU more concurrent store streams only thrash it (10 % slower at 24).  LDS the kernel never touches is
+    // the lever: a workgroup that asks for 1/n of a CU's 160 KB leaves room for n of them.  A count that is not a multiple
+    // of four takes workgroups of two wavefronts (row layouts only: the blocked layout wants four adjacent units per workgroup).
+    int bs = 256;
+    size_t cap_lds = 0;
+    if (g.itx_waves >= 8 && g.itx_waves <= 32) {
+        if (g.itx_waves % 4 != 0 && !g.blocked) bs = 128;
+        const int wgs = g.itx_waves / (bs / 64);
+        if (wgs >= 3) cap_lds = ((size_t)160 * 1024 / wgs - 1024) / 256 * 256;
+    }
+    const unsigned blocks = (unsigned)((lanes + bs - 1) / bs);
     InputMap mp{make_fastdiv((unsigned)g.tw), make_fastdiv((unsigned)g.th), make_fastdiv((unsigned)cols)};
     // 32-bit byte offsets: the input, one position plane of V (row layout) or one slab of V (blocked) below 4 GiB
     const long long in_elems = (long long)g.N * g.C * g.H * g.W;
     const long long v_elems = g.blocked ? (long long)g.cchunks * A * g.pg * 64 : (long long)g.C * g.ldp * (g.tiled ? A * A : 1);
     const bool wide = in_elems >= (1ll << 30) || v_elems >= (1ll << 30);
     const bool paired = bt_is_paired(BT, A);
-    const dim3 grid(blocks), block(256);
-    // Fewer workgroups per CU than the registers allow: the kernel is bound by the memory system, and past three or four
-    // workgroups per CU more concurrent store streams only thrash it (10 % slower at six).  LDS the kernel never touches is
-    // the lever: a workgroup that asks for 1/n of a CU's 160 KB leaves room for n of them.
-    const size_t cap_lds = (g.itx_cap >= 3 && g.itx_cap <= 8) ? ((size_t)160 * 1024 / g.itx_cap - 1024) / 256 * 256 : 0;
+    const dim3 grid(blocks), block(bs);
     auto launch = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, cap_lds, s, g, mp, m, x, V); };
     auto pick = [&](auto blocked_c, auto wide_c) {
         constexpr bool B = decltype(blocked_c)::value, W = decltype(wide_c)::value;
