@@ -110,7 +110,7 @@ int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
     }
     // One pass of 4 launches separates configurations that differ by 10 %, not those that differ by 2 %
     // (clock and cache state drift over the pass).  The configurations within 8 % of the fastest (at most four)
-    // are timed again in three interleaved rounds; the least time of each decides.
+    // are timed again in five interleaved rounds; the least time of each decides.
     if (!rc && best_ms > 0.f) {
         std::sort(timed.begin(), timed.end(), [](const auto& a, const auto& b) { return a.first < b.first; });
         size_t nf = 0;
@@ -127,7 +127,7 @@ int tune_gemm(GemmProblem p, hipStream_t s, GemmChoice* out)
                 }
                 if ((e = hipMalloc((void**)&part, (size_t)pf * sizeof(float))) != hipSuccess) rc = fail_hip(e, "hipMalloc split-K scratch");
             }
-            for (int round = 0; round < 3 && !rc; ++round)
+            for (int round = 0; round < 5 && !rc; ++round)
                 for (size_t i = 0; i < nf && !rc; ++i) {
                     p.variant = timed[i].second.variant;
                     p.splitk = timed[i].second.splitk;
