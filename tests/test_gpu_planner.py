@@ -161,3 +161,36 @@ def test_calibration_and_pruned_search():
     finally:
         m.set_device_model(**saved)
         m.cache_clear()
+
+
+def test_saved_pre_inference_results_plan_without_timing(tmp_path):
+    """mnn_conv_cache_save / _load: scheme choice (S), GEMM tile configuration (G) and the input transform's wavefront
+    cap (I) of a layer survive in a text file; planning the same layer from that file gives the same plan description
+    and is much faster than the timed search, and the planned layer still matches the oracle."""
+    import time
+    m = mnn()
+    layer = config_layers(3)[0]                              # 64 channels, 56 x 56, N = 32: a grid long enough for the cap to be tuned
+    m.cache_clear()
+    t0 = time.perf_counter()
+    with m.ConvPlan.for_layer(layer) as plan:
+        first, scheme = plan.describe(), plan.scheme
+    t_search = time.perf_counter() - t0
+    path = tmp_path / "plans.txt"
+    m.cache_save(str(path))
+    text = path.read_text()
+    tags = {line.split()[0] for line in text.splitlines()[1:] if line.strip()}
+    assert {"S", "G"} <= tags and (scheme.kind != m.SCHEME_WINOGRAD or "I" in tags)
+    m.cache_clear()
+    m.cache_load(str(path))
+    t0 = time.perf_counter()
+    with m.ConvPlan.for_layer(layer) as plan:
+        assert plan.describe() == first
+        t_cached = time.perf_counter() - t0
+        x, w, b = draw(layer)
+        y = plan.run(*(torch.from_numpy(a).cuda() for a in (x, w, b)))
+        torch.cuda.synchronize()
+    assert t_cached < 0.5 * t_search, (t_cached, t_search)
+    ref = oracle.conv2d(x, w, b, stride=layer.stride, pad=layer.pad, dil=layer.dil)
+    tol = 1e-3 if (scheme.kind == m.SCHEME_WINOGRAD and scheme.tile_n + layer.k_long - 1 > 6) else 1e-4
+    assert oracle.error_ratio(y.cpu().numpy(), ref) <= tol
+    m.cache_clear()
