@@ -178,35 +178,54 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, InputM
     const int ty = (int)t2 - (int)img * g.th;
     const int y0 = ty * g.n - g.pad_h;
     const int x0 = tx * g.n - g.pad_w;
-    // lane part of every x address (floats): the tile's top-left element.  Only dereferenced where it lies inside the
-    // image; for tiles over the top or left edge it is computed with wrap-around and corrected by the in-image (iy, ix).
-    const lane_off plane = (lane_off)((long long)img * g.C + c) * (lane_off)((long long)g.H * g.W);
+    // Loads.  A tile row is A consecutive floats: 16- and 8-byte loads at 4-byte alignment.  Tiles that hang over an edge
+    // of the image take the very same loads -- rows above or below the image are clamped to its first or last row, columns
+    // left or right of it simply read the neighbouring row or plane of the tensor -- and zero what lies outside afterwards:
+    // with 22 tiles per row every wavefront holds edge tiles, and a separate element-by-element path for them (64 predicated
+    // loads) would be issued by every wavefront.  Only a tile whose over-read would leave the tensor itself (the first rows of
+    // the first plane, the last of the last) takes that path.
+    const long long plane_ll = ((long long)img * g.C + c) * ((long long)g.H * g.W);
+    const lane_off plane = (lane_off)plane_ll;
+    const int ylo = y0 < 0 ? 0 : (y0 > g.H - 1 ? g.H - 1 : y0);
+    const int yhi = y0 + A - 1 < 0 ? 0 : (y0 + A - 1 > g.H - 1 ? g.H - 1 : y0 + A - 1);
+    const bool inside_tensor = plane_ll + (long long)ylo * g.W + x0 >= 0 &&
+                               plane_ll + (long long)yhi * g.W + x0 + A <= (long long)g.N * g.C * g.H * g.W;
+    const bool interior = (y0 >= 0) && (y0 + A <= g.H) && (x0 >= 0) && (x0 + A <= g.W);
 
     float d[A][A];
-    const bool interior = (y0 >= 0) && (y0 + A <= g.H) && (x0 >= 0) && (x0 + A <= g.W);
-    if (interior) {
-        // a tile row is A consecutive floats: 16- and 8-byte loads at 4-byte alignment
-        const lane_off xo = plane + (lane_off)(y0 * g.W + x0);
-        const lane_off xob = WIDE ? xo : xo * 4u;
-        auto at = [&](const float* uniform_base) -> const char* {
-            if constexpr (WIDE) return reinterpret_cast<const char*>(uniform_base + xob);
-            else return reinterpret_cast<const char*>(uniform_base) + xob;
-        };
+    if (inside_tensor) {
 #pragma unroll
         for (int i = 0; i < A; ++i) {
-            const float* rp = x + (long long)i * g.W;              // uniform
+            int iy = y0 + i;
+            iy = iy < 0 ? 0 : (iy > g.H - 1 ? g.H - 1 : iy);
+            // exact although x0 may be negative: the sum lies inside the tensor, and 32-bit arithmetic is modular
+            const lane_off ro = plane + (lane_off)(iy * g.W + x0);
+            const char* rp;
+            if constexpr (WIDE) rp = reinterpret_cast<const char*>(x + ro);
+            else rp = reinterpret_cast<const char*>(x) + ro * 4u;
             int j = 0;
 #pragma unroll
             for (; j + 4 <= A; j += 4) {
-                const Unaligned4 v = *reinterpret_cast<const Unaligned4*>(at(rp + j));
+                const Unaligned4 v = *reinterpret_cast<const Unaligned4*>(rp + j * 4);
                 d[i][j] = v.x; d[i][j + 1] = v.y; d[i][j + 2] = v.z; d[i][j + 3] = v.w;
             }
             if (j + 2 <= A) {
-                const Unaligned2 v = *reinterpret_cast<const Unaligned2*>(at(rp + j));
+                const Unaligned2 v = *reinterpret_cast<const Unaligned2*>(rp + j * 4);
                 d[i][j] = v.x; d[i][j + 1] = v.y;
                 j += 2;
             }
-            if (j < A) d[i][j] = *reinterpret_cast<const float*>(at(rp + j));
+            if (j < A) d[i][j] = *reinterpret_cast<const float*>(rp + j * 4);
+        }
+        if (!interior) {
+#pragma unroll
+            for (int i = 0; i < A; ++i) {
+                const bool rowok = (y0 + i >= 0) && (y0 + i < g.H);
+#pragma unroll
+                for (int j = 0; j < A; ++j) {
+                    const bool ok = rowok && (x0 + j >= 0) && (x0 + j < g.W);
+                    d[i][j] = ok ? d[i][j] : 0.f;
+                }
+            }
         }
     } else {
 #pragma unroll
@@ -217,7 +236,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, InputM
             for (int j = 0; j < A; ++j) {
                 const int ix = x0 + j;
                 const bool ok = rowok && (ix >= 0) && (ix < g.W);
-                d[i][j] = ok ? x[plane + (lane_off)(iy * g.W + ix)] : 0.f;
+                d[i][j] = ok ? x[plane_ll + (long long)iy * g.W + ix] : 0.f;
             }
         }
     }
