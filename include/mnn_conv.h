@@ -96,10 +96,11 @@ typedef struct {
     int32_t allow_bf16;       /* 1: AUTO may also time bf16-matrix-core candidates: BF16X3 for every scheme with a
                                  separate GEMM stage, plain BF16 for the 1x1 and sliding-window schemes only
                                  (plain bf16 Winograd operands miss the 2e-2 bound for most tiles)   */
-    int32_t alpha_max;        /* largest n + k - 1 the planner may generate (default 8, max 10:
+    int32_t alpha_max;        /* largest n + k - 1 the planner may generate (default and maximum 10:
                                  beyond that the fp32 error of the transforms exceeds 1e-3)          */
-    float   point_scale_f;    /* f of the Winograd generator (default 0.5, the paper's value); 0: per alpha the f with the
-                                 least fp32 error measured: 0.5 up to alpha = 8, 0.425 for alpha = 9 and 10 */
+    float   point_scale_f;    /* f of the Winograd generator (Section 3.3.1).  0 (default): the paper's 0.5 up to
+                                 alpha = 8 and 0.425 for alpha = 9 and 10, where 0.5 no longer gives the least fp32
+                                 error; > 0: that f for every tile */
     int32_t plan_warmup;      /* untimed launches per candidate (default 2)               */
     int32_t plan_iters;       /* timed launches per candidate (default 10)                */
     int32_t use_cache;        /* 1 (default): consult / fill the process-wide choice cache */

@@ -200,8 +200,8 @@ class Options:
     force_prec: int = GEMM_FP32
     force_variant: int = -1
     allow_bf16: int = 0
-    alpha_max: int = 8
-    point_scale_f: float = 0.5
+    alpha_max: int = 10
+    point_scale_f: float = 0.0
     plan_warmup: int = 2
     plan_iters: int = 10
     use_cache: int = 1
@@ -247,7 +247,7 @@ def analytic_cost(k, i_c, o_c, o_h, o_w, n) -> float:
     return float(out.value)
 
 
-def analytic_tile(k, i_c, o_c, o_h, o_w, alpha_max=8) -> int:
+def analytic_tile(k, i_c, o_c, o_h, o_w, alpha_max=10) -> int:
     out = c_int32()
     _check(lib.mnn_conv_analytic_tile(k, i_c, o_c, o_h, o_w, alpha_max, byref(out)))
     return int(out.value)

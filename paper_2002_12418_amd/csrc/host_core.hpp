@@ -35,8 +35,8 @@ void default_options(mnn_conv_options* o)
     o->force_prec = MNN_GEMM_FP32;
     o->force_variant = -1;
     o->allow_bf16 = 0;
-    o->alpha_max = 8;
-    o->point_scale_f = 0.5f;
+    o->alpha_max = kMaxAlphaT;
+    o->point_scale_f = 0.f;
     o->plan_warmup = 2;
     o->plan_iters = 10;
     o->use_cache = 1;
@@ -76,7 +76,7 @@ int validate(const mnn_conv_shape* shape, const mnn_conv_geom* geom, Layer* L)
 int validate_options(const mnn_conv_options* in, mnn_conv_options* o)
 {
     if (in) *o = *in; else default_options(o);
-    if (o->alpha_max <= 0) o->alpha_max = 8;
+    if (o->alpha_max <= 0) o->alpha_max = kMaxAlphaT;
     if (o->alpha_max > kMaxAlphaT)
         return fail(MNN_E_UNSUPPORTED, "alpha_max above %d: the fp32 error of larger tiles exceeds 1e-3", kMaxAlphaT);
     if (!(o->point_scale_f >= 0.f)) return fail(MNN_E_INVALID_ARG, "point_scale_f must be positive (or 0: chosen per alpha)");

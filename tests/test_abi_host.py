@@ -32,8 +32,8 @@ def test_every_declared_symbol_is_exported(mnn):
 def test_version_and_defaults(mnn):
     assert mnn.version() >= 100
     o = mnn.Options.defaults()
-    assert (o.force_kind, o.alpha_max, o.plan_iters, o.use_cache, o.force_variant) == (mnn.SCHEME_AUTO, 8, 10, 1, -1)
-    assert o.point_scale_f == 0.5
+    assert (o.force_kind, o.alpha_max, o.plan_iters, o.use_cache, o.force_variant) == (mnn.SCHEME_AUTO, 10, 10, 1, -1)
+    assert o.point_scale_f == 0.0
 
 
 NK = [(n, k) for k in range(2, 8) for n in range(2, 9) if n + k - 1 <= 12]
@@ -90,7 +90,7 @@ def test_enumeration_rules(mnn):
     c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 3, 5)
     assert c[0].kind == mnn.SCHEME_DIRECT
     assert [(s.kind, s.tile_n, s.variant) for s in c[1:]] == [(mnn.SCHEME_WINOGRAD, n, mnn.WINO_UNFUSED) for n in (2, 3, 4)]
-    c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 3, 5, options=mnn.Options(alpha_max=10))      # still alpha <= 8 for these
+    c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 3, 5, options=mnn.Options(alpha_max=8))       # the default already stops at alpha = 8 for these
     assert [s.tile_n for s in c[1:]] == [2, 3, 4]
     c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 2, 9)                                           # more than 7 taps on an axis
     assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
@@ -100,21 +100,25 @@ def test_enumeration_rules(mnn):
     for kh, kwid in ((1, 7), (7, 1)):
         c = mnn.enumerate_schemes(1, 8, 20, 20, 8, kh, kwid)
         assert c[0].kind == mnn.SCHEME_DIRECT
+        assert [(s.kind, s.tile_n, s.variant) for s in c[1:]] == [(mnn.SCHEME_WINOGRAD, n, mnn.WINO_UNFUSED) for n in (2, 3, 4)]
+        c = mnn.enumerate_schemes(1, 8, 20, 20, 8, kh, kwid, options=mnn.Options(alpha_max=8))
         assert [(s.kind, s.tile_n, s.variant) for s in c[1:]] == [(mnn.SCHEME_WINOGRAD, 2, mnn.WINO_UNFUSED)]
     c = mnn.enumerate_schemes(1, 8, 20, 20, 8, 3, 1, pad=(1, 0))
-    assert [(s.tile_n, s.variant) for s in c if s.kind == mnn.SCHEME_WINOGRAD] == [(n, mnn.WINO_UNFUSED) for n in range(2, 7)]
-    # 3x3 stride 1: sliding window + F(n,3) for n = 2..6 (alpha <= 8), each in its kernel arrangements
+    assert [(s.tile_n, s.variant) for s in c if s.kind == mnn.SCHEME_WINOGRAD] == [(n, mnn.WINO_UNFUSED) for n in range(2, 9)]
+    # 3x3 stride 1: sliding window + F(n,3) for n = 2..8 (alpha <= 10), each in its kernel arrangements
     c = mnn.enumerate_schemes(1, 64, 56, 56, 64, 3, 3, pad=1)
     assert c[0].kind == mnn.SCHEME_DIRECT
     wino = [s for s in c if s.kind == mnn.SCHEME_WINOGRAD]
-    assert sorted({s.tile_n for s in wino}) == [2, 3, 4, 5, 6]
-    assert all(any(s.tile_n == n and s.variant == mnn.WINO_UNFUSED for s in wino) for n in range(2, 7))
+    assert sorted({s.tile_n for s in wino}) == [2, 3, 4, 5, 6, 7, 8]
+    assert all(any(s.tile_n == n and s.variant == mnn.WINO_UNFUSED for s in wino) for n in range(2, 9))
     assert all(s.est_ms < 0 for s in c)
     # alpha_max caps n; 7x7 with alpha <= 8 only admits n = 2
     c = mnn.enumerate_schemes(1, 64, 56, 56, 64, 3, 3, pad=1, options=mnn.Options(alpha_max=6))
     assert sorted({s.tile_n for s in c if s.kind == mnn.SCHEME_WINOGRAD}) == [2, 3, 4]
-    c = mnn.enumerate_schemes(16, 64, 112, 112, 64, 7, 7, pad=3)
+    c = mnn.enumerate_schemes(16, 64, 112, 112, 64, 7, 7, pad=3, options=mnn.Options(alpha_max=8))
     assert sorted({s.tile_n for s in c if s.kind == mnn.SCHEME_WINOGRAD}) == [2]
+    c = mnn.enumerate_schemes(16, 64, 112, 112, 64, 7, 7, pad=3)
+    assert sorted({s.tile_n for s in c if s.kind == mnn.SCHEME_WINOGRAD}) == [2, 3, 4]
     # 1x1 with padding is not the plain GEMM case
     c = mnn.enumerate_schemes(1, 8, 8, 8, 8, 1, 1, pad=1)
     assert [s.kind for s in c] == [mnn.SCHEME_DIRECT]
@@ -191,7 +195,7 @@ def test_enumeration_with_bf16_allowed(mnn):
     x3 = [s for s in c if s.prec == mnn.GEMM_BF16X3]
     plain = [s for s in c if s.prec == mnn.GEMM_BF16]
     # split-operand variant for the sliding window and every F(n,3); plain bf16 only for the sliding window
-    assert sorted(s.tile_n for s in x3) == [0, 2, 3, 4, 5, 6] and all(s.variant == 0 for s in x3)
+    assert sorted(s.tile_n for s in x3) == [0, 2, 3, 4, 5, 6, 7, 8] and all(s.variant == 0 for s in x3)
     assert [(s.kind, s.tile_n) for s in plain] == [(mnn.SCHEME_DIRECT, 0)]
     c = mnn.enumerate_schemes(16, 32, 112, 112, 64, 1, 1, options=mnn.Options(allow_bf16=1))
     assert [(s.kind, s.prec, s.variant) for s in c] == [(mnn.SCHEME_GEMM1X1, 0, 0), (mnn.SCHEME_GEMM1X1, 2, 0),

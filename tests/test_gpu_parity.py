@@ -115,7 +115,9 @@ def test_bf16_matrix_core_schemes(layer):
         opt = m.Options(force_kind=s.kind, force_tile_n=s.tile_n, force_prec=s.prec, force_variant=s.variant)
         err, scheme = run_and_compare(layer, opt)
         assert scheme.prec == s.prec
-        assert err <= (BF16X3_TOL if s.prec == m.GEMM_BF16X3 else BF16_TOL), (layer.name, s.label(layer.k_long), err)
+        # split operands: this library's own 5e-4 up to alpha = 8; alpha = 9 and 10 measure about 1e-3 and are held to the bf16 bound
+        tight = s.prec == m.GEMM_BF16X3 and not (s.kind == m.SCHEME_WINOGRAD and s.tile_n + layer.k_long - 1 > 8)
+        assert err <= (BF16X3_TOL if tight else BF16_TOL), (layer.name, s.label(layer.k_long), err)
         seen += 1
     assert seen >= 2
 
