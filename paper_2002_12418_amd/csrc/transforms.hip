@@ -282,51 +282,97 @@ __global__ __launch_bounds__(256) void input_transform_kernel(WinoGeom g, InputM
 }
 
 // ---------------------------------------------------------------- output: y = A^T m A + bias
+struct OutputMap { FastDiv by_tw, by_th, by_p; };
+
+// One-dimensional inverse transform out = init + A^T in for an even number of points (same point sequence as above; the
+// host checks the matrix): the column of point 0 feeds only the first output, the column of infinity only the last,
+// and the columns of +p and -p are equal in the even rows and opposite in the odd ones -- so a pair of inputs enters
+// as its sum (even rows) and its difference (odd rows): half the multiply-adds of the dense product.
+template <int NT, int A>
+__device__ __forceinline__ void at_apply_paired(const MatArg<NT, A>& at, const float (&in)[A], float init, float (&out)[NT])
+{
+#pragma unroll
+    for (int i = 0; i < NT; ++i) out[i] = init;
+    out[0] = fmaf(at.v[0][0], in[0], out[0]);
+    out[NT - 1] = fmaf(at.v[NT - 1][A - 1], in[A - 1], out[NT - 1]);
+#pragma unroll
+    for (int m = 1; m < A - 1; m += 2) {
+        const float sum = in[m] + in[m + 1], dif = in[m] - in[m + 1];
+#pragma unroll
+        for (int i = 0; i < NT; ++i) out[i] = fmaf(at.v[i][m], (i & 1) ? dif : sum, out[i]);
+    }
+}
+
+// One lane per (output channel, tile), consecutive lanes consecutive tiles.  As in the input transform, every load and
+// store is a uniform base (tensor + position or row offset, scalar registers) plus one 32-bit lane offset in bytes.
 // STREAM: M is larger than the last-level cache, so this (its last) read goes past the caches instead of
 // evicting what the next kernel could still use; small M is read normally (it is still resident from the GEMM).
 // VEC: how a tile row is stored -- 0: one float at a time; 1: pairs (n and W_o even, 8-byte aligned base);
 // 2: one 16-byte store (n = 4, 4 | W_o, 16-byte aligned base).  A compile-time choice: with the choice made at run
 // time the unused store paths stay in the kernel and cost 10 % of its time.
-template <int NT, int A, bool STREAM, int VEC>
-__global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatArg<NT, A> at,
+// PAIRED: the A^T structure above holds (even A only).  WIDE: M or y is too large for 32-bit byte offsets.
+template <int NT, int A, bool STREAM, int VEC, bool PAIRED, bool WIDE>
+__global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, OutputMap mp, MatArg<NT, A> at,
                                                                const float* __restrict__ M,
                                                                const float* __restrict__ bias,
                                                                float* __restrict__ y)
 {
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)g.K * g.P) return;
-    const int kk = (int)(idx / g.P);
-    const int p = (int)(idx % g.P);
-    const int tx = p % g.tw;
-    const int t2 = p / g.tw;
-    const int ty = t2 % g.th;
-    const int img = t2 / g.th;
+    using lane_off = typename std::conditional<WIDE, long long, unsigned>::type;
+    const unsigned idx = blockIdx.x * 256u + threadIdx.x;        // < 2^31 (checked by the launcher)
+    const unsigned kk = fast_div(idx, mp.by_p);
+    if (kk >= (unsigned)g.K) return;
+    const unsigned p = idx - kk * mp.by_p.d;
+    const unsigned t2 = fast_div(p, mp.by_tw);
+    const int tx = (int)(p - t2 * (unsigned)g.tw);
+    const unsigned img = fast_div(t2, mp.by_th);
+    const int ty = (int)(t2 - img * (unsigned)g.th);
 
     const long long plane = g.tiled ? 64ll : (long long)g.K * g.ldp;
-    const float* mp = g.tiled ? M + (((long long)kk * g.pb + (p >> 6)) * (A * A)) * 64 + (p & 63) : M + (long long)kk * g.ldp + p;
-    // t = A^T m   (NT x A), accumulated row of m by row of m
-    float t[NT][A];
-#pragma unroll
-    for (int i = 0; i < NT; ++i)
-#pragma unroll
-        for (int b = 0; b < A; ++b) t[i][b] = 0.f;
+    const lane_off mo = g.tiled ? ((lane_off)kk * (lane_off)g.pb + (lane_off)(p >> 6)) * (lane_off)(A * A * 64) + (lane_off)(p & 63)
+                                : (lane_off)kk * (lane_off)g.ldp + (lane_off)p;
+    const lane_off mob = WIDE ? mo : mo * 4u;
     // All alpha^2 loads are issued before the first use: a wavefront then waits for memory once, not once per
     // row of m (the kernel is bound by that latency, not by registers: 4 or 8 wavefronts per SIMD make no difference).
     float m[A][A];
 #pragma unroll
     for (int a = 0; a < A; ++a)
 #pragma unroll
-        for (int b = 0; b < A; ++b)
-            m[a][b] = STREAM ? __builtin_nontemporal_load(mp + (long long)(a * A + b) * plane) : mp[(long long)(a * A + b) * plane];
+        for (int b = 0; b < A; ++b) {
+            const float* base = M + (a * A + b) * plane;                       // uniform: lives in scalar registers
+            const float* q;
+            if constexpr (WIDE) q = base + mob;
+            else q = reinterpret_cast<const float*>(reinterpret_cast<const char*>(base) + mob);
+            m[a][b] = STREAM ? __builtin_nontemporal_load(q) : *q;
+        }
     __builtin_amdgcn_sched_barrier(0);        // keep the compiler from sinking the loads between the multiply-adds
+    // t = A^T m   (NT x A)
+    float t[NT][A];
+    if constexpr (PAIRED) {
 #pragma unroll
-    for (int a = 0; a < A; ++a)
+        for (int b = 0; b < A; ++b) {
+            float col[A], out[NT];
+#pragma unroll
+            for (int a = 0; a < A; ++a) col[a] = m[a][b];
+            at_apply_paired<NT, A>(at, col, 0.f, out);
+#pragma unroll
+            for (int i = 0; i < NT; ++i) t[i][b] = out[i];
+        }
+    } else {
 #pragma unroll
         for (int i = 0; i < NT; ++i)
 #pragma unroll
-            for (int b = 0; b < A; ++b) t[i][b] = fmaf(at.v[i][a], m[a][b], t[i][b]);
+            for (int b = 0; b < A; ++b) t[i][b] = 0.f;
+#pragma unroll
+        for (int a = 0; a < A; ++a)
+#pragma unroll
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int b = 0; b < A; ++b) t[i][b] = fmaf(at.v[i][a], m[a][b], t[i][b]);
+    }
     const float bv = bias ? bias[kk] : 0.f;
-    float* yp = y + ((long long)img * g.K + kk) * g.Ho * g.Wo;
+    const lane_off yo = (((lane_off)img * (lane_off)g.K + (lane_off)kk) * (lane_off)g.Ho + (lane_off)(ty * NT)) * (lane_off)g.Wo +
+                        (lane_off)(tx * NT);
+    const lane_off yob = WIDE ? yo : yo * 4u;
     const bool whole_w = tx * NT + NT <= g.Wo;      // the tile does not hang over the right edge
     // A lane owns NT consecutive floats of NT output rows.  Stores of one float per lane would touch
     // 64*NT*4/64 cache lines per instruction; pairs halve the number of store instructions.
@@ -334,15 +380,22 @@ __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatAr
     for (int i = 0; i < NT; ++i) {
         const int oy = ty * NT + i;
         float o[NT];
+        if constexpr (PAIRED) {
+            at_apply_paired<NT, A>(at, t[i], bv, o);
+        } else {
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            float acc = bv;
+            for (int j = 0; j < NT; ++j) {
+                float acc = bv;
 #pragma unroll
-            for (int b = 0; b < A; ++b) acc = fmaf(t[i][b], at.v[j][b], acc);
-            o[j] = acc;
+                for (int b = 0; b < A; ++b) acc = fmaf(t[i][b], at.v[j][b], acc);
+                o[j] = acc;
+            }
         }
         if (oy >= g.Ho) continue;
-        float* row = yp + (long long)oy * g.Wo + tx * NT;
+        float* rbase = y + (long long)i * g.Wo;                                // uniform
+        float* row;
+        if constexpr (WIDE) row = rbase + yob;
+        else row = reinterpret_cast<float*>(reinterpret_cast<char*>(rbase) + yob);
         if constexpr (NT == 4 && VEC == 2) {
             {                         // 16-byte aligned tile rows, no ragged column
                 *reinterpret_cast<float4*>(row) = make_float4(o[0], o[1], o[2], o[3]);
@@ -369,6 +422,18 @@ __global__ __launch_bounds__(256) void output_transform_kernel(WinoGeom g, MatAr
         for (int j = 0; j < NT; ++j)
             if (tx * NT + j < g.Wo) row[j] = o[j];
     }
+}
+
+// Whether A^T (row-major NT x A) has the structure at_apply_paired relies on, exactly.
+inline bool at_is_paired(const float* AT, int NT, int A)
+{
+    if (A % 2 || NT < 2) return false;
+    for (int i = 1; i < NT; ++i) if (AT[i * A] != 0.f) return false;                       // point 0: first output only
+    for (int i = 0; i < NT - 1; ++i) if (AT[i * A + A - 1] != 0.f) return false;           // infinity: last output only
+    for (int m = 1; m < A - 1; m += 2)
+        for (int i = 0; i < NT; ++i)
+            if (AT[i * A + m + 1] != ((i & 1) ? -AT[i * A + m] : AT[i * A + m])) return false;
+    return true;
 }
 
 // Whether B^T (row-major A x A) has the structure bt_apply_paired relies on, exactly.
@@ -437,26 +502,43 @@ hipError_t launch_output_t(const WinoGeom& g, const float* AT, const float* M, c
     for (int i = 0; i < NT; ++i)
         for (int j = 0; j < A; ++j) m.v[i][j] = AT[i * A + j];
     const long long total = (long long)g.K * g.P;
+    if (total <= 0 || total + 256 >= (1ll << 31)) return hipErrorInvalidValue;
     const unsigned blocks = (unsigned)((total + 255) / 256);
     // 8-byte stores need every tile row start 8-byte aligned: even n, even W_o, aligned base
     int vec2 = (NT % 2 == 0) && (g.Wo % 2 == 0) && ((reinterpret_cast<uintptr_t>(y) & 7u) == 0);
     if (NT == 4 && (g.Wo % 4 == 0) && ((reinterpret_cast<uintptr_t>(y) & 15u) == 0)) vec2 = 2;   // whole-tile float4 rows
     // 256 MB of last-level cache on this part; well above half of it nothing of M survives until it is read
     const bool stream = (double)A * A * g.K * g.ldp * sizeof(float) > 160e6;
-    auto launch = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, s, g, m, M, bias, y); };
-    if constexpr (NT == 4) {
-        if (vec2 == 2) {
-            if (stream) launch(output_transform_kernel<NT, A, true, 2>); else launch(output_transform_kernel<NT, A, false, 2>);
-            return hipGetLastError();
+    // 32-bit byte offsets: what a lane adds to a uniform base -- all of M in the tiled layout, one position plane of it in
+    // the row layout, all of y -- stays below 4 GiB
+    const long long m_lane_elems = (long long)g.K * g.ldp * (g.tiled ? A * A : 1);
+    const long long y_elems = (long long)g.N * g.K * g.Ho * g.Wo;
+    const bool wide = m_lane_elems >= (1ll << 30) || y_elems >= (1ll << 30);
+    const bool paired = at_is_paired(AT, NT, A);
+    OutputMap mp{make_fastdiv((unsigned)g.tw), make_fastdiv((unsigned)g.th), make_fastdiv((unsigned)g.P)};
+    auto launch = [&](auto kernel) { hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, s, g, mp, m, M, bias, y); };
+    // a tensor that needs 64-bit offsets is far larger than the caches: the wide form exists for streamed reads only
+    auto pick = [&](auto vec_c) {
+        constexpr int V = decltype(vec_c)::value;
+        if constexpr (A % 2 == 0) {
+            if (paired) {
+                if (wide) launch(output_transform_kernel<NT, A, true, V, true, true>);
+                else if (stream) launch(output_transform_kernel<NT, A, true, V, true, false>);
+                else launch(output_transform_kernel<NT, A, false, V, true, false>);
+                return;
+            }
         }
+        if (wide) launch(output_transform_kernel<NT, A, true, V, false, true>);
+        else if (stream) launch(output_transform_kernel<NT, A, true, V, false, false>);
+        else launch(output_transform_kernel<NT, A, false, V, false, false>);
+    };
+    if constexpr (NT == 4) {
+        if (vec2 == 2) { pick(std::integral_constant<int, 2>{}); return hipGetLastError(); }
     }
     if constexpr (NT % 2 == 0) {
-        if (vec2) {
-            if (stream) launch(output_transform_kernel<NT, A, true, 1>); else launch(output_transform_kernel<NT, A, false, 1>);
-            return hipGetLastError();
-        }
+        if (vec2) { pick(std::integral_constant<int, 1>{}); return hipGetLastError(); }
     }
-    if (stream) launch(output_transform_kernel<NT, A, true, 0>); else launch(output_transform_kernel<NT, A, false, 0>);
+    pick(std::integral_constant<int, 0>{});
     return hipGetLastError();
 }
 

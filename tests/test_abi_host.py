@@ -53,6 +53,29 @@ def test_generator_equals_exact_rationals_rounded_once(mnn, n, k, f):
         np.testing.assert_array_equal(got, want32)
 
 
+@pytest.mark.parametrize("n,k", [(n, k) for k in range(2, 8) for n in range(2, 9) if n + k - 1 <= 10 and (n + k) % 2 == 1])
+@pytest.mark.parametrize("f", [0.5, 0.425, 1.0])
+def test_even_alpha_matrices_have_the_sum_and_difference_structure(mnn, n, k, f):
+    """What the transform kernels exploit for an even number of points 0, +f, -f, ..., infinity (half the
+    multiply-adds): in B^T the row of point 0 is an even polynomial, the row of infinity an odd one, and the rows of +p
+    and -p share their even coefficients and have opposite odd ones; in A^T the column of point 0 feeds the first
+    output only, the column of infinity the last only, and the columns of +p and -p are equal in even rows and
+    opposite in odd ones.  The kernels check this at launch and fall back to the dense product; here it is pinned
+    for every generated pair of matrices, so that the fast path is the one the parity tests run."""
+    AT, G, BT = mnn.get_transforms(n, k, f)
+    a = n + k - 1
+    assert a % 2 == 0
+    assert np.all(BT[0, 1::2] == 0) and np.all(BT[a - 1, 0::2] == 0)
+    for m in range(1, a - 1, 2):
+        assert BT[m, 0] == BT[m, a - 1] == BT[m + 1, 0] == BT[m + 1, a - 1] == 0
+        sign = np.where(np.arange(1, a - 1) % 2 == 1, -1.0, 1.0).astype(np.float32)
+        np.testing.assert_array_equal(BT[m + 1, 1:a - 1], sign * BT[m, 1:a - 1])
+    assert np.all(AT[1:, 0] == 0) and np.all(AT[:n - 1, a - 1] == 0)
+    rows = np.where(np.arange(n) % 2 == 1, -1.0, 1.0).astype(np.float32)
+    for m in range(1, a - 1, 2):
+        np.testing.assert_array_equal(AT[:, m + 1], rows * AT[:, m])
+
+
 def test_generator_rejects_bad_arguments(mnn):
     with pytest.raises(mnn.MnnError) as e:
         mnn.get_transforms(8, 7, 0.5)           # alpha = 14 > 12
