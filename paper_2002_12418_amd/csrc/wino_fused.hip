@@ -50,7 +50,7 @@ __device__ __forceinline__ void wait_vmcnt()
 }
 
 template <int A, int NT_, int WTM, int WTN, int WM, int WN, int BKG, int NS>
-__global__ __launch_bounds__(WM * WN * 64, 2) void wino_fused_kernel(WinoGeom g, MatArg<NT_, A> at,
+__global__ __launch_bounds__(WM * WN * 64, (WM * WN > 8 ? 1 : 2)) void wino_fused_kernel(WinoGeom g, MatArg<NT_, A> at,
                                                                   const float* __restrict__ Ub,
                                                                   const float* __restrict__ Vb,
                                                                   const float* __restrict__ bias,
@@ -321,6 +321,9 @@ constexpr int bkg_for(int alpha) { return alpha <= 6 ? 4 : 2; }
 constexpr int kStages = 2;
 
 constexpr bool fits_big(int n, int k) { return (2 * (4 * (n + k - 1) + 4 * n * n)) <= 192; }
+// 64 x 64 blocks as sixteen wavefronts of one tile each (four per SIMD: 128 registers), for the tiles whose two-tile
+// wavefronts do not fit
+constexpr bool fits_big16(int n, int k) { return !fits_big(n, k) && 4 * (n + k - 1) + 4 * n * n <= 108; }
 // one 16x16 tile per wavefront must leave room for two wavefronts per SIMD (256 registers each)
 constexpr bool fits_small(int n, int k) { return 4 * (n + k - 1) + 4 * n * n <= 230; }
 
@@ -332,7 +335,7 @@ bool wino_fused_available(int n, int k)
     return n >= 2 && k >= 2 && a <= kMaxAlphaT && fits_small(n, k) && winograd_kernels_available(n, k);
 }
 
-bool wino_fused_has_big_block(int n, int k) { return wino_fused_available(n, k) && fits_big(n, k); }
+bool wino_fused_has_big_block(int n, int k) { return wino_fused_available(n, k) && (fits_big(n, k) || fits_big16(n, k)); }
 
 namespace {
 
@@ -343,6 +346,9 @@ hipError_t dispatch_fused(const WinoGeom& g, int config, const float* AT, const 
     if (g.n == NN && g.k == KK) {                                                                \
         if constexpr (fits_big(NN, KK)) {                                                        \
             if (config == 1) return launch_fused_t<NN, KK, 2, 1, 2, 4, bkg_for(NN + KK - 1), kStages>(g, AT, Ub, Vb, bias, y, s, r);  \
+        }                                                                                        \
+        if constexpr (fits_big16(NN, KK)) {                                                      \
+            if (config == 1) return launch_fused_t<NN, KK, 1, 1, 4, 4, bkg_for(NN + KK - 1), kStages>(g, AT, Ub, Vb, bias, y, s, r);  \
         }                                                                                        \
         return launch_fused_t<NN, KK, 1, 1, 2, 2, bkg_for(NN + KK - 1), kStages>(g, AT, Ub, Vb, bias, y, s, r);                       \
     }
@@ -396,7 +402,10 @@ hipError_t big_block_share(const WinoGeom& g, int* p_big)
 }  // namespace
 
 // config 0: 32 channels x 32 tiles per workgroup (4 wavefronts, one 16x16 tile each);
-// config 1: 64 channels x 64 tiles (8 wavefronts, two tiles each along K), where registers allow.
+// config 1: 64 channels x 64 tiles: 8 wavefronts of two tiles each along K where two tiles fit 256 registers, else 16
+// wavefronts of one tile each where one tile fits 128 (F(4,6), F(4,7): the kernel is paced by what a CU can copy
+// from L2 per cycle, and the larger block halves the bytes per multiply -- 190 -> 173 us for F(4,7) on 16 x 64 x 112 x 112
+// although its 196 workgroups, one per CU, leave 60 CUs idle).
 //
 // The 64 x 64 workgroups are few and long (two per CU): a grid of 1.5 times what the device holds runs as two
 // rounds, the second half empty.  When the last round would be at most 60 % full, config 1 therefore covers only the
