@@ -99,19 +99,22 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN > 8 ? 1 : 2)) void wino_fuse
     const long long v_step = (long long)BKG * A * g.pg * 64;
 
     // Per-lane source offsets of this wavefront's copies inside a chunk: LDS image [ccl][a][group][64].
-    // A wavefront whose copy index falls past the end repeats an earlier copy (same bytes to the same
-    // place), so that every wavefront has exactly LPW copies in flight per chunk and one vmcnt fits all.
+    // Copy j of wavefront w is piece j * NW + w.  With two stages every wait is for all copies, so a wavefront simply
+    // skips the pieces past the end (a wavefront-uniform branch); with more stages the waits count copies, every
+    // wavefront must have exactly LPW of them in flight per chunk, and a piece past the end repeats an earlier one
+    // (same bytes to the same place).
+    constexpr bool EXACT = (NS == 2);
     int uo[JU], vo[JV], uq[JU], vq[JV];
 #pragma unroll
     for (int j = 0; j < JU; ++j) {
-        uq[j] = (j * NW + wave) % UQ;
-        const int s = uq[j] * 64 + lane;                     // 16-byte slot
+        uq[j] = EXACT ? j * NW + wave : (j * NW + wave) % UQ;
+        const int s = (uq[j] % UQ) * 64 + lane;              // 16-byte slot
         uo[j] = (s / (MG * 16)) * g.kg * 64 + (s % (MG * 16)) * 4;
     }
 #pragma unroll
     for (int j = 0; j < JV; ++j) {
-        vq[j] = (j * NW + wave) % VQ;
-        const int s = vq[j] * 64 + lane;
+        vq[j] = EXACT ? j * NW + wave : (j * NW + wave) % VQ;
+        const int s = (vq[j] % VQ) * 64 + lane;
         vo[j] = (s / (PG * 16)) * g.pg * 64 + (s % (PG * 16)) * 4;
     }
 
@@ -122,10 +125,12 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN > 8 ? 1 : 2)) void wino_fuse
         const float* vg = Vp + t * v_step;
 #pragma unroll
         for (int j = 0; j < JU; ++j)
-            __builtin_amdgcn_global_load_lds((glb_void*)(ug + uo[j]), (lds_void*)(ustage(st) + uq[j] * 256), 16, 0, 0);
+            if (!EXACT || (j + 1) * NW <= UQ || uq[j] < UQ)
+                __builtin_amdgcn_global_load_lds((glb_void*)(ug + uo[j]), (lds_void*)(ustage(st) + uq[j] * 256), 16, 0, 0);
 #pragma unroll
         for (int j = 0; j < JV; ++j)
-            __builtin_amdgcn_global_load_lds((glb_void*)(vg + vo[j]), (lds_void*)(vstage(st) + vq[j] * 256), 16, 0, 0);
+            if (!EXACT || (j + 1) * NW <= VQ || vq[j] < VQ)
+                __builtin_amdgcn_global_load_lds((glb_void*)(vg + vo[j]), (lds_void*)(vstage(st) + vq[j] * 256), 16, 0, 0);
     };
 
     floatx4 acc[A][WTM][WTN];
@@ -147,24 +152,35 @@ __global__ __launch_bounds__(WM * WN * 64, (WM * WN > 8 ? 1 : 2)) void wino_fuse
 #pragma unroll
                     for (int jj = 0; jj < NT_; ++jj) Y[i][j][r][ii][jj] = 0.f;
 
+    // The operands of position idx + 1 are read from LDS before the MFMAs of position idx are issued, so that a
+    // wavefront's matrix instructions follow each other without an LDS round trip between them.
     auto multiply = [&](int st) {
         const float* us = ustage(st) + (wm * WTM) * 64 + lane;
         const float* vs = vstage(st) + (wn * WTN) * 64 + lane;
+        constexpr int NP = BKG * A;            // (channel group, position) pairs of a chunk, in LDS order
+        float av[2][WTM], bv[2][WTN];
 #pragma unroll
-        for (int ccl = 0; ccl < BKG; ++ccl)
+        for (int i = 0; i < WTM; ++i) av[0][i] = us[i * 64];
 #pragma unroll
-            for (int a = 0; a < A; ++a) {
-                float av[WTM], bv[WTN];
+        for (int j = 0; j < WTN; ++j) bv[0][j] = vs[j * 64];
 #pragma unroll
-                for (int i = 0; i < WTM; ++i) av[i] = us[((ccl * A + a) * MG + i) * 64];
+        for (int idx = 0; idx < NP; ++idx) {
+            const int cur = idx & 1, nxt = cur ^ 1;
+            if (idx + 1 < NP) {
 #pragma unroll
-                for (int j = 0; j < WTN; ++j) bv[j] = vs[((ccl * A + a) * PG + j) * 64];
+                for (int i = 0; i < WTM; ++i) av[nxt][i] = us[((idx + 1) * MG + i) * 64];
 #pragma unroll
-                for (int i = 0; i < WTM; ++i)
-#pragma unroll
-                    for (int j = 0; j < WTN; ++j)
-                        acc[a][i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[j], acc[a][i][j], 0, 0, 0);
+                for (int j = 0; j < WTN; ++j) bv[nxt][j] = vs[((idx + 1) * PG + j) * 64];
             }
+            __builtin_amdgcn_sched_barrier(0);     // the scheduler would otherwise pair each read with its own MFMA again
+            const int a = idx % A;
+#pragma unroll
+            for (int i = 0; i < WTM; ++i)
+#pragma unroll
+                for (int j = 0; j < WTN; ++j)
+                    acc[a][i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[cur][i], bv[cur][j], acc[a][i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     // Y += (A^T m[:, b]) (x) A^T[:, b] for every (k, p) pair this lane owns; accumulators restart at 0.
