@@ -193,6 +193,34 @@ def test_fused_64x64_with_a_tail_of_32x32_workgroups():
     assert torch.equal(outs[m.WINO_FUSED_OUT_64], outs[m.WINO_FUSED_OUT_32])
 
 
+@pytest.mark.parametrize("case", [
+    # name, N, C, H, W, K, k, pad, n
+    ("f47_ragged", 2, 13, 37, 41, 70, 7, 3, 4),          # channels, output channels and tiles all ragged
+    ("f46_ragged", 1, 9, 30, 26, 33, 6, 2, 4),
+    ("f47_tail", 3, 4, 320, 320, 64, 7, 3, 4),           # 300 blocks of 64 tiles: 256 as 64 x 64, 44 as 32 x 32 workgroups
+], ids=lambda c: c[0])
+def test_fused_64x64_as_sixteen_one_tile_wavefronts(case):
+    """F(4,6) and F(4,7) do not fit two 16 x 16 tiles per wavefront; their 64 x 64 blocks are sixteen wavefronts of one
+    tile each.  Whole tensor against the oracle, and the same bits as the 32 x 32 arrangement."""
+    m = mnn()
+    name, N, C, H, W, K, k, pad, n = case
+    layer = ConvLayer(name, N, C, H, W, K, k, k, 1, pad, 1, (-1.0, 1.0), BASE_SEED + 880 + k + C)
+    x, w, b = draw(layer)
+    ref = oracle.conv2d(x, w, b, stride=1, pad=pad)
+    xd, wd, bd = (torch.from_numpy(a).cuda() for a in (x, w, b))
+    outs = {}
+    for variant in (m.WINO_FUSED_OUT_64, m.WINO_FUSED_OUT_32):
+        opt = m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=n, force_variant=variant)
+        with m.ConvPlan.for_layer(layer, options=opt) as plan:
+            assert plan.scheme.variant == variant
+            y = torch.full(plan.out_shape, float("nan"), dtype=torch.float32, device="cuda")
+            plan.run(xd, wd, bd, y)
+            torch.cuda.synchronize()
+        assert oracle.error_ratio(y.cpu().numpy(), ref) <= 1e-3
+        outs[variant] = y
+    assert torch.equal(outs[m.WINO_FUSED_OUT_64], outs[m.WINO_FUSED_OUT_32])
+
+
 def test_weights_rewritten_behind_the_same_pointer_are_prepared_again():
     """The prepared weights (G w G^T, the transposed weights of the other schemes) are cached per weight pointer.
     New values behind an unchanged pointer -- an in-place update, a rewrite torch does not count -- must not be served
