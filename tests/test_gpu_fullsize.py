@@ -138,6 +138,41 @@ def test_operands_of_two_gib_take_the_wide_loader():
         del y
 
 
+def test_winograd_tensors_of_four_gib_take_the_wide_transforms():
+    """Input and output of 2^30 elements each: past the 32-bit byte offsets of the transform kernels, which must
+    switch to their 64-bit lane offsets (input transform: every row load, clamped edge rows included; output transform:
+    every tile-row store).  Separate kernels and the fused arrangement; oracle at sampled output coordinates."""
+    from conv_workloads import ConvLayer, BASE_SEED
+    m = mnn()
+    n, c, hw, k = 1, 16, 8192, 16
+    assert n * c * hw * hw >= 2**30 and n * k * hw * hw >= 2**30
+    rng = np.random.Generator(np.random.PCG64(BASE_SEED + 9950))
+    x = rng.random((n, c, hw, hw), dtype=np.float32) * 2 - 1
+    xd = torch.from_numpy(x).cuda()
+    layer = ConvLayer("wide_wino", n, c, hw, hw, k, 3, 3, 1, 1, 1, (-1.0, 1.0), BASE_SEED + 9951)
+    w = rng.normal(0, np.sqrt(2.0 / (9 * c)), (k, c, 3, 3)).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, k).astype(np.float32)
+    wd, bd = torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda()
+    coords = sample_coords(layer.out_shape, 4096, np.random.default_rng(6))
+    ref = oracle.conv2d_points(x, w, b, coords, stride=1, pad=1)
+    idx = tuple(torch.from_numpy(coords[:, i].copy()).cuda() for i in range(4))
+    for tile_n, variant in ((4, m.WINO_UNFUSED), (2, m.WINO_FUSED_OUT_32)):
+        print(f"[wide] F({tile_n},3) variant {variant} ...", flush=True)
+        o = m.Options(force_kind=m.SCHEME_WINOGRAD, force_tile_n=tile_n, force_variant=variant)
+        with m.ConvPlan.for_layer(layer, options=o) as plan:
+            y = torch.full(plan.out_shape, float("nan"), device="cuda")
+            plan.run(xd, wd, bd, y)
+            torch.cuda.synchronize()
+            desc = plan.describe()
+        got = y[idx].cpu().numpy()
+        assert np.isfinite(got).all()
+        err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+        print(f"[wide] {desc} err={err:.2e}", flush=True)
+        assert err <= 1e-4
+        assert bool(torch.isfinite(y[0, :, :64]).all()) and bool(torch.isfinite(y[0, :, -64:]).all())
+        del y
+
+
 def test_rect_layers_full_tensor():
     """The factorised 7-tap layers bench.py reports (rectangular_kernels), planner's choice, whole output."""
     from conv_workloads import rect_layers
