@@ -74,37 +74,44 @@ def recorded_traffic(cfg, kernel_desc):
     return None, "no recorded rocprofv3 counter run matches the kernel this run found dominant (layer, scheme and tile configuration)"
 
 
-def cpu_baseline(layers):
+def cpu_baseline(layers, gpu_outputs=None):
     """The float64 oracle, as it stands, timed on the host cores over a bounded sample of the same workload:
     whole images of every layer (images are independent), as many as fit about 1.5 s of wall time per layer,
-    i.e. roughly 10-30 s of CPU work on a 16-core host."""
+    i.e. roughly 10-30 s of CPU work on a 16-core host.  The oracle's results for those images are there anyway, so
+    the outputs the timed kernels left on the GPU for the same images are compared with them (gpu_vs_oracle)."""
+    import numpy as np
     import oracle
     from conv_workloads import draw
     flops, secs = 0.0, 0.0
     names = []
+    errs = {}
     cores = oracle.num_threads()
     per_layer_s = 1.5
     for layer in layers:
+        x, w, b = draw(layer)
         # a first single image gives the rate; then size the sample for the wall-time budget
-        one = layer.with_batch(1)
-        x, w, b = draw(one)
         t0 = time.perf_counter()
-        oracle.conv2d(x, w, b, stride=one.stride, pad=one.pad, dil=one.dil)
+        oracle.conv2d(x[:1], w, b, stride=layer.stride, pad=layer.pad, dil=layer.dil)
         t1 = time.perf_counter() - t0
         keep = int(max(1, min(layer.n, per_layer_s / max(t1, 1e-4))))
-        sample = layer.with_batch(keep)
-        x, w, b = draw(sample)
+        xs = np.ascontiguousarray(x[:keep])
         # small layers finish in a fraction of the budget: repeat the pass so that the sample is not noise
         reps = int(max(1, min(50, round(0.5 * per_layer_s / max(t1 * keep, 1e-4)))))
         t0 = time.perf_counter()
         for _ in range(reps):
-            oracle.conv2d(x, w, b, stride=sample.stride, pad=sample.pad, dil=sample.dil)
+            ref = oracle.conv2d(xs, w, b, stride=layer.stride, pad=layer.pad, dil=layer.dil)
         secs += time.perf_counter() - t0
-        flops += sample.direct_flops * reps
-        names.append(f"{sample.name}[N={sample.n}]x{reps}")
-    return {"value": round(flops / secs / 1e9, 2), "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": "float64 direct-convolution passes over " + ", ".join(names),
-            "seconds": round(secs, 3), "cpu_seconds": round(secs * cores, 1)}
+        flops += layer.with_batch(keep).direct_flops * reps
+        names.append(f"{layer.name}[N={keep}]x{reps}")
+        if gpu_outputs is not None and layer.name in gpu_outputs:
+            errs[layer.name] = float(f"{oracle.error_ratio(gpu_outputs[layer.name][:keep].cpu().numpy(), ref):.3e}")
+    out = {"value": round(flops / secs / 1e9, 2), "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
+           "sample": "float64 direct-convolution passes over " + ", ".join(names),
+           "seconds": round(secs, 3), "cpu_seconds": round(secs * cores, 1)}
+    if errs:
+        # max|y_gpu - y_oracle| / max|y_oracle| over the sampled images: what the timed kernels wrote against the oracle
+        out["gpu_vs_oracle"] = errs
+    return out
 
 
 def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
@@ -185,6 +192,7 @@ def run_workload(cfg, steps, warmup, opt, stream, mnn, torch, detailed=True):
     res["per_layer"] = per_layer
     res["stage_tot"] = stage_tot
     res["kernels"] = kernels
+    res["outputs"] = {layer.name: y for layer, _plan, _x, _w, _b, y in work}    # what the timed kernels wrote (device tensors)
     for _, plan, *_rest in work:
         plan.close()
     return res
@@ -444,7 +452,7 @@ def main():
     if args.plan_file:
         mnn.cache_save(args.plan_file)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layers)
+        out["cpu_baseline"] = cpu_baseline(layers, main_res.get("outputs"))
     print(json.dumps(out))
 
 
